@@ -1,0 +1,152 @@
+"""ctypes loader for the float64 CPU checker in vfa_oracle.c.
+
+TEST INFRASTRUCTURE ONLY.  Tests, the smoke check and the benchmark's cpu_baseline
+leg may import this; the GPU library and its Python binding never do.  Nothing here
+imports the GPU package.  The wrappers below only marshal numpy arrays; every step of
+the arithmetic is in the C file, which cites the passages it follows.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "vfa_oracle.c")
+_LIB = os.path.join(_HERE, "libvfa_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile vfa_oracle.c with gcc (plain C, -O2, OpenMP over query blocks)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-fopenmp", "-shared", "-fPIC", "-Wall", "-o", _LIB, _SRC, "-lm"]
+        )
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.oracle_num_threads.restype = ctypes.c_int
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def _p(a, ct):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ct))
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a
+
+
+def brute(Q, K, V, causal: bool, scale: float | None = None):
+    """One head, whole N x N matrix. Q,K,V [N,d]. Returns (P [N,N], O [N,d], LSE [N])."""
+    Q, K, V = _f32(Q), _f32(K), _f32(V)
+    N, d = Q.shape
+    scale = 1.0 / math.sqrt(d) if scale is None else scale
+    P = np.empty((N, N)); O = np.empty((N, d)); L = np.empty(N)
+    rc = _load().oracle_brute(_p(Q, ctypes.c_float), _p(K, ctypes.c_float), _p(V, ctypes.c_float),
+                              N, d, int(causal), ctypes.c_double(scale),
+                              _p(P, ctypes.c_double), _p(O, ctypes.c_double), _p(L, ctypes.c_double))
+    assert rc == 0
+    return P, O, L
+
+
+def _dims(Q, K):
+    B, Hq, N, d = Q.shape
+    Hkv = K.shape[1]
+    assert K.shape == (B, Hkv, N, d) and Hq % Hkv == 0
+    return B, Hq, Hkv, N, d
+
+
+def exact(Q, K, V, block_m: int, causal: bool, blocks, scale: float | None = None):
+    """Exact attention rows of the listed query blocks. Returns (O, LSE, M)."""
+    Q, K, V = _f32(Q), _f32(K), _f32(V)
+    B, Hq, Hkv, N, d = _dims(Q, K)
+    scale = 1.0 / math.sqrt(d) if scale is None else scale
+    blocks = np.ascontiguousarray(blocks, dtype=np.int32)
+    n = len(blocks)
+    O = np.full((n, block_m, d), np.nan); L = np.full((n, block_m), np.nan); M = np.full((n, block_m), np.nan)
+    rc = _load().oracle_exact(_p(Q, ctypes.c_float), _p(K, ctypes.c_float), _p(V, ctypes.c_float),
+                              B, Hq, Hkv, N, d, block_m, int(causal), ctypes.c_double(scale), n,
+                              _p(blocks, ctypes.c_int), _p(O, ctypes.c_double), _p(L, ctypes.c_double),
+                              _p(M, ctypes.c_double))
+    assert rc == 0
+    return O, L, M
+
+
+def sabsmax(K, block_n: int, repr_mode: int = 0):
+    """Key-block summaries [B,Hkv,Tc,d] (float64). repr_mode 0 is the method's sabsmax."""
+    K = _f32(K)
+    B, Hkv, N, d = K.shape
+    Tc = -(-N // block_n)
+    out = np.empty((B, Hkv, Tc, d))
+    rc = _load().oracle_sabsmax(_p(K, ctypes.c_float), B, Hkv, N, d, block_n, repr_mode, _p(out, ctypes.c_double))
+    assert rc == 0
+    return out
+
+
+def visit_list(N, block_m, block_n, causal, i, n_sink, n_local, reorder=True):
+    Tc = -(-N // block_n)
+    j = np.zeros(Tc, dtype=np.int32); s = np.zeros(Tc, dtype=np.int32)
+    n = _load().oracle_visit_list(N, block_m, block_n, int(causal), i, n_sink, n_local, int(reorder),
+                                  _p(j, ctypes.c_int), _p(s, ctypes.c_int))
+    return j[:n].copy(), s[:n].copy()
+
+
+def blocks(Q, K, V, block_m, block_n, causal, blocks, *, n_sink=1, n_local=1, use_minit=True,
+           reorder=True, freeze=True, vsa=False, skip_threshold_nats=None, scale=None,
+           krepr=None, m_override=None, want_traj=False):
+    """Alg. 1 (default), Alg. 2 (vsa=True) or online softmax on every block
+    (use_minit=False, reorder=False, freeze=False) for the listed query blocks.
+    Returns a dict: O, LSE, m_init, m_final, mask, margin, counters[, traj]."""
+    Q, K, V = _f32(Q), _f32(K), _f32(V)
+    B, Hq, Hkv, N, d = _dims(Q, K)
+    scale = 1.0 / math.sqrt(d) if scale is None else scale
+    Tc = -(-N // block_n)
+    blk = np.ascontiguousarray(blocks, dtype=np.int32)
+    n = len(blk)
+    if use_minit and krepr is None:
+        krepr = sabsmax(K, block_n)
+    if krepr is not None:
+        krepr = np.ascontiguousarray(krepr, dtype=np.float64)
+    if m_override is not None:
+        m_override = np.ascontiguousarray(m_override, dtype=np.float64)
+        assert m_override.shape == (n, block_m)
+    ln_lambda = -float(skip_threshold_nats) if vsa else 0.0
+    if vsa:
+        assert skip_threshold_nats is not None and skip_threshold_nats > 0
+    O = np.full((n, block_m, d), np.nan); L = np.full((n, block_m), np.nan)
+    mi = np.full((n, block_m), np.nan); mf = np.full((n, block_m), np.nan)
+    mask = np.zeros((n, Tc), dtype=np.uint8); margin = np.empty((n, Tc))
+    cnt = np.zeros((n, 4), dtype=np.int64)
+    traj = np.full((n, Tc, block_m, 2), np.nan) if want_traj else None
+    rc = _load().oracle_blocks(
+        _p(Q, ctypes.c_float), _p(K, ctypes.c_float), _p(V, ctypes.c_float), B, Hq, Hkv, N, d,
+        block_m, block_n, int(causal), ctypes.c_double(scale), _p(krepr, ctypes.c_double),
+        n_sink, n_local, int(use_minit), int(reorder), int(freeze), int(vsa), ctypes.c_double(ln_lambda),
+        n, _p(blk, ctypes.c_int), _p(m_override, ctypes.c_double), _p(O, ctypes.c_double), _p(L, ctypes.c_double),
+        _p(mi, ctypes.c_double), _p(mf, ctypes.c_double), _p(mask, ctypes.c_uint8), _p(margin, ctypes.c_double),
+        _p(cnt, ctypes.c_int64), _p(traj, ctypes.c_double))
+    assert rc == 0
+    out = dict(O=O, LSE=L, m_init=mi, m_final=mf, mask=mask, margin=margin, counters=cnt)
+    if want_traj:
+        out["traj"] = traj
+    return out
+
+
+def fa2(Q, K, V, block_m, block_n, causal, blocks_, scale=None, want_traj=False):
+    """FA column of Table 1: ascending order, exact-max update on every block."""
+    return blocks(Q, K, V, block_m, block_n, causal, blocks_, n_sink=0, n_local=0, use_minit=False,
+                  reorder=False, freeze=False, scale=scale, want_traj=want_traj)

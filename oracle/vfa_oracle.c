@@ -1,0 +1,392 @@
+/*
+ * vfa_oracle.c -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * A plain, slow, float64 CPU implementation of what the VFA / VSA attention
+ * forward path computes.  It exists so that the GPU library can be checked
+ * against something written directly from the paper.  It shares no code,
+ * header, table or helper with the GPU library, and the GPU library never
+ * calls it.  Only tests, the smoke check and the benchmark's cpu_baseline
+ * leg may load it.
+ *
+ * What each function follows:
+ *   oracle_brute      Sec. 2.1: S = Q K^T / sqrt(d), P = softmax(S), O = P V, with
+ *                     the whole N x N matrix materialised (tiny inputs only).
+ *   oracle_exact      the same definition, row by row in two passes (max, then
+ *                     sum), for chosen query blocks of a large problem.
+ *   oracle_sabsmax    Alg. 1 "precompute key-block representations" and the
+ *                     sentence defining sabsmax in "Step 1".
+ *   oracle_visit_list Alg. 1 main-loop order <1, i, 2, 3, ...> (Step 2),
+ *                     generalised as stated below.
+ *   oracle_blocks     Alg. 1 (VFA), Alg. 2 (VSA) and the FA column of Table 1
+ *                     (online softmax on every block), selected by switches.
+ *
+ * Readings taken where the paper is silent or inconsistent (all 0-based here;
+ * the paper counts blocks from 1):
+ *   R1  The 1/sqrt(d) scale of Sec. 2.1 / Table 1 "MUL" applies to S and to the
+ *       approximate scores alike (Alg. 1 omits it in both).
+ *   R2  sabsmax tie (+a and -a both of largest magnitude): the positive one.
+ *   R3  One summary per main-loop key block (T_c1 = T_c, as the paper sets it).
+ *   R4  Causal: m-init runs over visible key blocks only (j <= j_hi(i)).
+ *   R5  Special set = the first n_sink blocks, and the local set L(i) = the key
+ *       blocks overlapping the query block's own token range, plus the
+ *       n_local-1 blocks just before them; each block is visited once; order
+ *       inside each group ascending.  With block_m == block_n and
+ *       n_sink = n_local = 1 this is the paper's {1, i}.
+ *   R6  Causal masking: S = -inf where key index > query index; a fully masked
+ *       row keeps its state.
+ *   R7  VSA: a block is skipped iff the skip inequality holds for ALL rows of
+ *       the query block (rows with no visible key in the block vote "skip").
+ *       PARITY UNPINNED: the paper prints no value that fixes this reading;
+ *       it is supported only by the row-skip variant's description.
+ *   R8  VSA: the test uses m* = max(m_prev, m~); a skipped block leaves the
+ *       state unchanged, also when it is a special block.
+ *   R9  All blocks of a row skipped => l = 0 => O = 0, LSE = -inf.
+ *   R10 LSE = m + ln(l) (natural log, scaled scores).  The paper outputs only
+ *       O; PARITY UNPINNED by the paper, pinned here by the brute-force
+ *       definition ln(sum exp(s)).
+ *
+ * All tensors are row-major: Q [B,Hq,N,d], K,V [B,Hkv,N,d] as float32 on input
+ * (bf16-representable values widen exactly), everything inside is double.
+ * Query head h reads KV head h / (Hq/Hkv).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+typedef struct {
+    const float *Q, *K, *V;
+    int B, Hq, Hkv, N, d;
+    int block_m, block_n;
+    int causal;
+    double scale;
+} prob_t;
+
+static int ceil_div(int a, int b) { return (a + b - 1) / b; }
+static int imin(int a, int b) { return a < b ? a : b; }
+static int imax(int a, int b) { return a > b ? a : b; }
+
+static const float *q_row(const prob_t *p, int b, int h, int r) {
+    return p->Q + (((size_t)b * p->Hq + h) * p->N + r) * p->d;
+}
+static const float *k_row(const prob_t *p, int b, int h, int c) {
+    int hkv = h / (p->Hq / p->Hkv);
+    return p->K + (((size_t)b * p->Hkv + hkv) * p->N + c) * p->d;
+}
+static const float *v_row(const prob_t *p, int b, int h, int c) {
+    int hkv = h / (p->Hq / p->Hkv);
+    return p->V + (((size_t)b * p->Hkv + hkv) * p->N + c) * p->d;
+}
+
+/* s = scale * <Q[r], K[c]>   (Sec. 2.1) */
+static double score(const prob_t *p, int b, int h, int r, int c) {
+    const float *q = q_row(p, b, h, r), *k = k_row(p, b, h, c);
+    double acc = 0.0;
+    for (int t = 0; t < p->d; ++t) acc += (double)q[t] * (double)k[t];
+    return p->scale * acc;
+}
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ------------------------------------------------------------------ */
+/* Brute force, one head: S [N,N], P = softmax rows, O = P V.          */
+/* P_out [N,N] and O_out [N,d], LSE_out [N]; Q,K,V are [N,d].           */
+int oracle_brute(const float *Q, const float *K, const float *V, int N, int d, int causal,
+                 double scale, double *P_out, double *O_out, double *LSE_out) {
+    prob_t p = {Q, K, V, 1, 1, 1, N, d, N, N, causal, scale};
+    double *S = (double *)malloc((size_t)N * N * sizeof(double));
+    if (!S) return -1;
+    for (int r = 0; r < N; ++r)
+        for (int c = 0; c < N; ++c)
+            S[(size_t)r * N + c] = (causal && c > r) ? -INFINITY : score(&p, 0, 0, r, c);
+    for (int r = 0; r < N; ++r) {
+        double mx = -INFINITY, sum = 0.0;
+        for (int c = 0; c < N; ++c) mx = fmax(mx, S[(size_t)r * N + c]);
+        for (int c = 0; c < N; ++c) sum += exp(S[(size_t)r * N + c] - mx);
+        for (int c = 0; c < N; ++c) P_out[(size_t)r * N + c] = exp(S[(size_t)r * N + c] - mx) / sum;
+        LSE_out[r] = mx + log(sum);
+        for (int t = 0; t < d; ++t) {
+            double acc = 0.0;
+            for (int c = 0; c < N; ++c) acc += P_out[(size_t)r * N + c] * (double)V[(size_t)c * d + t];
+            O_out[(size_t)r * d + t] = acc;
+        }
+    }
+    free(S);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Exact attention for listed query blocks.  blocks = nblk triples (b, h, i).
+ * O [nblk, block_m, d], LSE [nblk, block_m], M [nblk, block_m] (true row max).
+ * Rows beyond N are left untouched.                                     */
+int oracle_exact(const float *Q, const float *K, const float *V, int B, int Hq, int Hkv, int N,
+                 int d, int block_m, int causal, double scale, int nblk, const int *blocks,
+                 double *O, double *LSE, double *M) {
+    prob_t p = {Q, K, V, B, Hq, Hkv, N, d, block_m, block_m, causal, scale};
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int n = 0; n < nblk; ++n) {
+        int b = blocks[3 * n], h = blocks[3 * n + 1], i = blocks[3 * n + 2];
+        double *s = (double *)malloc((size_t)N * sizeof(double));
+        for (int rr = 0; rr < block_m; ++rr) {
+            int r = i * block_m + rr;
+            if (r >= N) break;
+            int nvis = causal ? r + 1 : N;
+            double mx = -INFINITY, sum = 0.0;
+            for (int c = 0; c < nvis; ++c) { s[c] = score(&p, b, h, r, c); mx = fmax(mx, s[c]); }
+            for (int c = 0; c < nvis; ++c) { s[c] = exp(s[c] - mx); sum += s[c]; }
+            double *o = O + ((size_t)n * block_m + rr) * d;
+            for (int t = 0; t < d; ++t) o[t] = 0.0;
+            for (int c = 0; c < nvis; ++c) {
+                const float *v = v_row(&p, b, h, c);
+                for (int t = 0; t < d; ++t) o[t] += s[c] * (double)v[t];
+            }
+            for (int t = 0; t < d; ++t) o[t] /= sum;
+            LSE[(size_t)n * block_m + rr] = mx + log(sum);
+            M[(size_t)n * block_m + rr] = mx;
+        }
+        free(s);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* sabsmax (Alg. 1 precompute; Step 1): per key block and dimension, the
+ * element of largest absolute value with its sign; reading R2 on ties.
+ * repr_mode: 0 sabsmax (the method); 1 per-dim max; 2 per-dim mean;
+ * 3 unsigned absmax (the three ablated summaries).  out [B,Hkv,Tc,d].    */
+int oracle_sabsmax(const float *K, int B, int Hkv, int N, int d, int block_n, int repr_mode,
+                   double *out) {
+    int Tc = ceil_div(N, block_n);
+    for (int bh = 0; bh < B * Hkv; ++bh)
+        for (int j = 0; j < Tc; ++j)
+            for (int t = 0; t < d; ++t) {
+                int c0 = j * block_n, c1 = imin(N, c0 + block_n);
+                double best = (double)K[((size_t)bh * N + c0) * d + t];
+                double sum = 0.0, mx = -INFINITY, amx = 0.0;
+                for (int c = c0; c < c1; ++c) {
+                    double x = (double)K[((size_t)bh * N + c) * d + t];
+                    if (fabs(x) > fabs(best) || (fabs(x) == fabs(best) && x > best)) best = x;
+                    sum += x;
+                    mx = fmax(mx, x);
+                    amx = fmax(amx, fabs(x));
+                }
+                double r = best;
+                if (repr_mode == 1) r = mx;
+                if (repr_mode == 2) r = sum / (c1 - c0);
+                if (repr_mode == 3) r = amx;
+                out[((size_t)bh * Tc + j) * d + t] = r;
+            }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Block geometry (reading R5).  a_lo..a_hi: key blocks overlapping the
+ * query block's own tokens; j_hi: last visible key block.              */
+static void geometry(int N, int block_m, int block_n, int causal, int i, int *a_lo, int *a_hi,
+                     int *j_hi) {
+    int r0 = i * block_m, r1 = imin(N, r0 + block_m) - 1;
+    *a_lo = r0 / block_n;
+    *a_hi = r1 / block_n;
+    *j_hi = causal ? *a_hi : ceil_div(N, block_n) - 1;
+}
+
+/* Visit order of Alg. 1's main loop for query block i.
+ * reorder = 1: sink blocks, then local blocks, then the rest, each once.
+ * reorder = 0: plain ascending order ("w/o reorder" ablation, and FA).
+ * special_out[k] = 1 where the block takes the exact-max update.
+ * Returns the number of visited blocks; arrays must hold Tc entries.    */
+int oracle_visit_list(int N, int block_m, int block_n, int causal, int i, int n_sink, int n_local,
+                      int reorder, int *j_out, int *special_out) {
+    int a_lo, a_hi, j_hi;
+    geometry(N, block_m, block_n, causal, i, &a_lo, &a_hi, &j_hi);
+    int Tc = ceil_div(N, block_n);
+    char *is_special = (char *)calloc((size_t)Tc, 1), *seen = (char *)calloc((size_t)Tc, 1);
+    for (int j = 0; j < n_sink && j <= j_hi; ++j) is_special[j] = 1;
+    if (n_local > 0)
+        for (int j = imax(0, a_lo - (n_local - 1)); j <= imin(a_hi, j_hi); ++j) is_special[j] = 1;
+    int n = 0;
+    if (reorder) {
+        for (int j = 0; j < n_sink && j <= j_hi; ++j)
+            if (!seen[j]) { seen[j] = 1; j_out[n] = j; special_out[n++] = 1; }
+        if (n_local > 0)
+            for (int j = imax(0, a_lo - (n_local - 1)); j <= imin(a_hi, j_hi); ++j)
+                if (!seen[j]) { seen[j] = 1; j_out[n] = j; special_out[n++] = 1; }
+    }
+    for (int j = 0; j <= j_hi; ++j)
+        if (!seen[j]) { seen[j] = 1; j_out[n] = j; special_out[n++] = is_special[j]; }
+    free(is_special);
+    free(seen);
+    return n;
+}
+
+/* ------------------------------------------------------------------ */
+/* One query block of Alg. 1 / Alg. 2 / FA.  See oracle_blocks for the
+ * meaning of the switches and outputs.                                  */
+typedef struct {
+    int n_sink, n_local, use_minit, reorder, freeze, vsa;
+    double ln_lambda;
+} opts_t;
+
+static void one_block(const prob_t *p, const opts_t *o, const double *krepr, int b, int h, int i,
+                      const double *m_override, double *O, double *LSE, double *m_init_out,
+                      double *m_final_out, uint8_t *mask_row, double *margin_row,
+                      int64_t *counters, double *traj) {
+    const int N = p->N, d = p->d, Br = p->block_m, Bc = p->block_n;
+    const int Tc = ceil_div(N, Bc);
+    const int r0 = i * Br, nr = imin(Br, N - r0);
+    const int hkv = h / (p->Hq / p->Hkv);
+    int a_lo, a_hi, j_hi;
+    geometry(N, Br, Bc, p->causal, i, &a_lo, &a_hi, &j_hi);
+
+    double *m = (double *)malloc((size_t)Br * sizeof(double));
+    double *l = (double *)calloc((size_t)Br, sizeof(double));
+    double *acc = (double *)calloc((size_t)Br * d, sizeof(double));
+    double *S = (double *)malloc((size_t)Br * Bc * sizeof(double));
+    double *mt = (double *)malloc((size_t)Br * sizeof(double));
+    int *vj = (int *)malloc((size_t)Tc * sizeof(int)), *vs = (int *)malloc((size_t)Tc * sizeof(int));
+
+    /* m-initialisation (Alg. 1: score_approx = Q_i k_repr_j^T, elementwise max over j) */
+    for (int rr = 0; rr < nr; ++rr) {
+        double mi = -INFINITY;
+        if (o->use_minit) {
+            const float *q = q_row(p, b, h, r0 + rr);
+            for (int j = 0; j <= j_hi; ++j) {
+                const double *kr = krepr + (((size_t)b * p->Hkv + hkv) * Tc + j) * d;
+                double a = 0.0;
+                for (int t = 0; t < d; ++t) a += (double)q[t] * kr[t];
+                mi = fmax(mi, p->scale * a);
+            }
+        }
+        if (m_override) mi = m_override[rr];
+        m[rr] = mi;
+        if (m_init_out) m_init_out[rr] = mi;
+    }
+    if (mask_row) for (int j = 0; j < Tc; ++j) mask_row[j] = 2; /* not visited */
+    if (margin_row) for (int j = 0; j < Tc; ++j) margin_row[j] = NAN;
+
+    int nv = oracle_visit_list(N, Br, Bc, p->causal, i, o->n_sink, o->n_local, o->reorder, vj, vs);
+    for (int k = 0; k < nv; ++k) {
+        const int j = vj[k];
+        const int special = o->freeze ? vs[k] : 1;
+        const int c0 = j * Bc, nc = imin(Bc, N - c0);
+        /* S_ij = scale * Q_i K_j^T, masked entries -inf */
+        for (int rr = 0; rr < nr; ++rr)
+            for (int cc = 0; cc < nc; ++cc) {
+                int r = r0 + rr, c = c0 + cc;
+                S[rr * Bc + cc] = (p->causal && c > r) ? -INFINITY : score(p, b, h, r, c);
+            }
+        counters[0] += 1; /* visited tiles */
+        if (o->vsa || special) {
+            for (int rr = 0; rr < nr; ++rr) {
+                double x = -INFINITY;
+                for (int cc = 0; cc < nc; ++cc) x = fmax(x, S[rr * Bc + cc]);
+                mt[rr] = x;
+            }
+            counters[1] += 1; /* rowmax executed on this tile */
+        }
+        if (o->vsa) {
+            /* Alg. 2: m* = max(m_prev, m~); skip iff m~ - m* < ln(lambda) for all rows */
+            double worst = -INFINITY;
+            for (int rr = 0; rr < nr; ++rr) {
+                double diff;
+                if (mt[rr] == -INFINITY) diff = -INFINITY;
+                else diff = mt[rr] - fmax(m[rr], mt[rr]);
+                worst = fmax(worst, diff);
+            }
+            if (margin_row) margin_row[j] = worst - o->ln_lambda;
+            if (worst < o->ln_lambda) {
+                if (mask_row) mask_row[j] = 1;
+                counters[3] += 1; /* skipped tiles */
+                if (traj) for (int rr = 0; rr < nr; ++rr) { traj[((size_t)k * Br + rr) * 2] = m[rr]; traj[((size_t)k * Br + rr) * 2 + 1] = l[rr]; }
+                continue;
+            }
+        }
+        if (mask_row) mask_row[j] = 0;
+        if (special) counters[2] += 1; /* rescale chain executed on this tile */
+        for (int rr = 0; rr < nr; ++rr) {
+            double m_use = m[rr], alpha = 1.0;
+            if (special) {
+                double m_new = fmax(m[rr], mt[rr]);
+                alpha = (m_new == -INFINITY) ? 1.0 : exp(m[rr] - m_new);
+                m_use = m_new;
+            }
+            double rowsum = 0.0;
+            double *orow = acc + (size_t)rr * d;
+            if (special) {
+                for (int t = 0; t < d; ++t) orow[t] *= alpha;
+                l[rr] *= alpha;
+            }
+            for (int cc = 0; cc < nc; ++cc) {
+                double s = S[rr * Bc + cc];
+                double pt = (s == -INFINITY) ? 0.0 : exp(s - m_use);
+                rowsum += pt;
+                const float *v = v_row(p, b, h, c0 + cc);
+                for (int t = 0; t < d; ++t) orow[t] += pt * (double)v[t];
+            }
+            l[rr] += rowsum;
+            m[rr] = m_use;
+        }
+        if (traj) for (int rr = 0; rr < nr; ++rr) { traj[((size_t)k * Br + rr) * 2] = m[rr]; traj[((size_t)k * Br + rr) * 2 + 1] = l[rr]; }
+    }
+    /* final normalisation O = O / l */
+    for (int rr = 0; rr < nr; ++rr) {
+        for (int t = 0; t < d; ++t) O[(size_t)rr * d + t] = (l[rr] > 0.0) ? acc[(size_t)rr * d + t] / l[rr] : 0.0;
+        LSE[rr] = (l[rr] > 0.0) ? m[rr] + log(l[rr]) : -INFINITY;
+        if (m_final_out) m_final_out[rr] = m[rr];
+    }
+    free(m); free(l); free(acc); free(S); free(mt); free(vj); free(vs);
+}
+
+/* Listed query blocks of VFA (Alg. 1), VSA (Alg. 2) or FA (Table 1, FA column).
+ *
+ *   blocks      nblk triples (b, h, i)
+ *   krepr       [B,Hkv,Tc,d] from oracle_sabsmax (ignored when use_minit = 0)
+ *   n_sink, n_local, use_minit   as in the method (use_minit = 0: m starts at -inf)
+ *   reorder     1 = sink, local, rest (the method); 0 = ascending order
+ *   freeze      1 = exact-max update on special blocks only (the method);
+ *               0 = on every block (FA / online softmax)
+ *   vsa         1 = Alg. 2 skip test on every visited block, threshold ln_lambda < 0
+ *   m_override  NULL, or [nblk, block_m] values that replace m_init (test hook for
+ *               the identity "any finite seed gives the exact result")
+ *   O [nblk,block_m,d]  LSE [nblk,block_m]
+ *   m_init_out, m_final_out  NULL or [nblk, block_m]
+ *   mask_out    NULL or [nblk, Tc] uint8: 0 computed, 1 skipped, 2 not visited
+ *   margin_out  NULL or [nblk, Tc]: max_r(m~ - m*) - ln_lambda (skip iff < 0), NaN if not visited
+ *   counters    [nblk, 4] int64: tiles visited, rowmax executions, rescale executions, skipped
+ *   traj        NULL or [nblk, Tc, block_m, 2]: (m, l) after the k-th visited block
+ * FA is (use_minit=0, reorder=0, freeze=0, vsa=0).                       */
+int oracle_blocks(const float *Q, const float *K, const float *V, int B, int Hq, int Hkv, int N,
+                  int d, int block_m, int block_n, int causal, double scale, const double *krepr,
+                  int n_sink, int n_local, int use_minit, int reorder, int freeze, int vsa,
+                  double ln_lambda, int nblk, const int *blocks, const double *m_override,
+                  double *O, double *LSE, double *m_init_out, double *m_final_out,
+                  uint8_t *mask_out, double *margin_out, int64_t *counters, double *traj) {
+    if (Hq % Hkv != 0 || block_m <= 0 || block_n <= 0) return -1;
+    if (use_minit && !krepr && !m_override) return -1;
+    prob_t p = {Q, K, V, B, Hq, Hkv, N, d, block_m, block_n, causal, scale};
+    opts_t o = {n_sink, n_local, use_minit, reorder, freeze, vsa, ln_lambda};
+    const int Tc = ceil_div(N, block_n);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int n = 0; n < nblk; ++n) {
+        int64_t *cn = counters + (size_t)n * 4;
+        cn[0] = cn[1] = cn[2] = cn[3] = 0;
+        one_block(&p, &o, krepr, blocks[3 * n], blocks[3 * n + 1], blocks[3 * n + 2],
+                  m_override ? m_override + (size_t)n * block_m : NULL,
+                  O + (size_t)n * block_m * d, LSE + (size_t)n * block_m,
+                  m_init_out ? m_init_out + (size_t)n * block_m : NULL,
+                  m_final_out ? m_final_out + (size_t)n * block_m : NULL,
+                  mask_out ? mask_out + (size_t)n * Tc : NULL,
+                  margin_out ? margin_out + (size_t)n * Tc : NULL, cn,
+                  traj ? traj + (size_t)n * Tc * block_m * 2 : NULL);
+    }
+    return 0;
+}

@@ -1,0 +1,438 @@
+"""Pins for the CPU oracle: each test ties one part of it to something the paper or the
+mathematics fixes (a library routine, a closed form, an invariant, a hand-worked value),
+so that a dropped term, wrong sign, wrong index or transposed operand fails somewhere."""
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+
+from paper_2604_12798_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rnd(seed, *shape):
+    return np.random.default_rng(seed).standard_normal(shape).astype(np.float32)
+
+
+def lib_attention(Q, K, V, causal, scale):
+    """Whole-matrix softmax attention from library routines (numpy matmul, scipy softmax)."""
+    S = scale * (Q.astype(np.float64) @ K.astype(np.float64).T)
+    if causal:
+        S = np.where(np.tril(np.ones_like(S, dtype=bool)), S, -np.inf)
+    P = scipy.special.softmax(S, axis=1)
+    return P, P @ V.astype(np.float64), scipy.special.logsumexp(S, axis=1), S
+
+
+# ------------------------------------------------------------------ brute force and exact rows
+@pytest.mark.parametrize("N,d,causal", [(7, 3, False), (7, 3, True), (33, 16, True), (64, 8, False)])
+def test_brute_matches_library_softmax(oracle, N, d, causal):
+    Q, K, V = rnd(1, N, d), rnd(2, N, d), rnd(3, N, d)
+    scale = 0.37
+    P, O, L = oracle.brute(Q, K, V, causal, scale)
+    Pl, Ol, Ll, _ = lib_attention(Q, K, V, causal, scale)
+    assert np.abs(P - Pl).max() < 1e-14
+    assert np.abs(O - Ol).max() < 1e-13
+    assert np.abs(L - Ll).max() < 1e-13
+    assert np.abs(P.sum(1) - 1).max() < 1e-13                      # rows of P sum to one
+    if causal:
+        assert np.all(np.triu(P, 1) == 0)                          # no weight on future keys
+
+
+def test_hand_worked_two_keys(oracle):
+    # s = q*k with scale 1: scores (0, ln 2) -> P = (1/3, 2/3); V = (3, 6) -> O = 5, LSE = ln 3
+    Q = np.array([[1.0], [1.0]], np.float32)
+    K = np.array([[0.0], [math.log(2.0)]], np.float32)
+    V = np.array([[3.0], [6.0]], np.float32)
+    P, O, L = oracle.brute(Q, K, V, False, 1.0)
+    k1 = float(K[1, 0])
+    p1 = math.exp(k1) / (1 + math.exp(k1))
+    assert abs(P[1, 1] - p1) < 1e-15 and abs(O[1, 0] - (3 + 3 * p1)) < 1e-14
+    assert abs(O[1, 0] - 5.0) < 1e-6 and abs(L[1] - math.log(3.0)) < 1e-6
+    P, O, L = oracle.brute(Q, K, V, True, 1.0)
+    assert O[0, 0] == 3.0 and L[0] == 0.0                          # causal: row 0 sees key 0 only
+
+
+def test_uniform_keys_closed_form(oracle):
+    # identical keys => uniform P => O = (prefix) mean of V, LSE = s + ln(n)
+    N, d = 40, 8
+    Q, V = rnd(4, 1, 2, N, d), rnd(5, 1, 1, N, d)
+    K = np.tile(rnd(6, 1, 1, 1, d), (1, 1, N, 1))
+    blocks = np.array([(0, h, i) for h in range(2) for i in range(3)], np.int32)
+    O, L, M = oracle.exact(Q, K, V, 16, True, blocks)
+    for n, (b, h, i) in enumerate(blocks):
+        for rr in range(16):
+            r = i * 16 + rr
+            if r >= N:
+                assert np.isnan(O[n, rr]).all()
+                continue
+            s = float(Q[0, h, r].astype(np.float64) @ K[0, 0, 0].astype(np.float64)) / math.sqrt(d)
+            assert np.abs(O[n, rr] - V[0, 0, : r + 1].astype(np.float64).mean(0)).max() < 1e-13
+            assert abs(L[n, rr] - (s + math.log(r + 1))) < 1e-12 and abs(M[n, rr] - s) < 1e-12
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("g", [1, 2, 4])
+def test_exact_rows_match_brute_gqa(oracle, causal, g):
+    B, Hkv, N, d, bm = 2, 2, 50, 12, 16
+    Hq = Hkv * g
+    Q, K, V = rnd(7, B, Hq, N, d), rnd(8, B, Hkv, N, d), rnd(9, B, Hkv, N, d)
+    blocks = np.array([(b, h, i) for b in range(B) for h in range(Hq) for i in range(4)], np.int32)
+    O, L, M = oracle.exact(Q, K, V, bm, causal, blocks)
+    for n, (b, h, i) in enumerate(blocks):
+        _, Ob, Lb, S = lib_attention(Q[b, h], K[b, h // g], V[b, h // g], causal, 1 / math.sqrt(d))
+        rows = slice(i * bm, min(N, (i + 1) * bm))
+        nr = rows.stop - rows.start
+        assert np.abs(O[n, :nr] - Ob[rows]).max() < 1e-13
+        assert np.abs(L[n, :nr] - Lb[rows]).max() < 1e-13
+        assert np.abs(M[n, :nr] - S[rows].max(1)).max() < 1e-13
+
+
+# ------------------------------------------------------------------ sabsmax
+def test_sabsmax_golden(oracle):
+    for line in open(os.path.join(GOLDEN, "sabsmax_example.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        lhs, rhs = line.split("=>")
+        block = np.array([[float(x) for x in row.split()] for row in lhs.split(";")], np.float32)
+        want = np.array([float(x) for x in rhs.split()])
+        got = oracle.sabsmax(block[None, None], block.shape[0])[0, 0, 0]
+        assert np.array_equal(got, want), (block, got, want)
+
+
+def test_sabsmax_properties(oracle):
+    K = rnd(10, 2, 3, 70, 5)
+    for bn in (16, 32):
+        R = oracle.sabsmax(K, bn)
+        Tc = -(-70 // bn)
+        assert R.shape == (2, 3, Tc, 5)
+        for j in range(Tc):
+            blk = K[:, :, j * bn: min(70, (j + 1) * bn)].astype(np.float64)
+            assert np.array_equal(np.abs(R[:, :, j]), np.abs(blk).max(2))          # magnitude = absmax
+            assert np.all((blk == R[:, :, j][:, :, None, :]).any(2))               # an element of the block
+    # order of keys inside a block is irrelevant
+    perm = np.random.default_rng(0).permutation(16)
+    K2 = K[:, :, :64].copy().reshape(2, 3, 4, 16, 5)[:, :, :, perm].reshape(2, 3, 64, 5)
+    assert np.array_equal(oracle.sabsmax(K[:, :, :64], 16), oracle.sabsmax(K2, 16))
+
+
+# ------------------------------------------------------------------ visit order
+def test_visit_order_golden(oracle):
+    for line in open(os.path.join(GOLDEN, "visit_order.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        lhs, rhs = line.split(":")
+        Tc, i = (int(x) for x in lhs.split())
+        want = [int(x) - 1 for x in rhs.split()]
+        j, s = oracle.visit_list(Tc * 8, 8, 8, False, i - 1, 1, 1)
+        assert list(j) == want
+        assert [int(x) for x in s] == [1 if (b == 0 or b == i - 1) else 0 for b in want]
+
+
+@pytest.mark.parametrize("bm,bn", [(8, 8), (16, 8), (8, 16), (24, 8)])
+@pytest.mark.parametrize("causal", [False, True])
+def test_visit_list_is_a_permutation_of_visible_blocks(oracle, bm, bn, causal):
+    N = 100
+    Tc = -(-N // bn)
+    for n_sink, n_local in [(0, 0), (1, 1), (2, 1), (1, 3), (0, 2), (3, 0)]:
+        for i in range(-(-N // bm)):
+            j, s = oracle.visit_list(N, bm, bn, causal, i, n_sink, n_local)
+            last_row = min(N, (i + 1) * bm) - 1
+            j_hi = last_row // bn if causal else Tc - 1
+            assert sorted(j) == list(range(j_hi + 1))                               # each visible block once
+            a_lo, a_hi = (i * bm) // bn, last_row // bn
+            special = {b for b in range(min(n_sink, j_hi + 1))}
+            if n_local > 0:
+                special |= set(range(max(0, a_lo - (n_local - 1)), min(a_hi, j_hi) + 1))
+            assert {int(b) for b, f in zip(j, s) if f} == special
+            k = len(special)
+            assert set(int(b) for b in j[:k]) == special                            # special blocks come first
+            assert list(j[k:]) == sorted(j[k:])                                      # the rest ascending
+            j0, s0 = oracle.visit_list(N, bm, bn, causal, i, n_sink, n_local, reorder=False)
+            assert list(j0) == list(range(j_hi + 1))                                 # "w/o reorder": ascending
+            assert {int(b) for b, f in zip(j0, s0) if f} == special
+
+
+# ------------------------------------------------------------------ m-initialisation
+def test_m_init_is_max_of_q_dot_summaries(oracle):
+    B, Hq, Hkv, N, d, bm, bn = 1, 4, 2, 96, 8, 16, 8
+    Q, K, V = rnd(11, B, Hq, N, d), rnd(12, B, Hkv, N, d), rnd(13, B, Hkv, N, d)
+    R = oracle.sabsmax(K, bn)
+    blocks = np.array([(0, h, i) for h in range(Hq) for i in range(N // bm)], np.int32)
+    for causal in (False, True):
+        out = oracle.blocks(Q, K, V, bm, bn, causal, blocks)
+        for n, (b, h, i) in enumerate(blocks):
+            j_hi = ((i + 1) * bm - 1) // bn if causal else N // bn - 1
+            approx = (Q[0, h, i * bm:(i + 1) * bm].astype(np.float64) @ R[0, h // 2, : j_hi + 1].T) / math.sqrt(d)
+            assert np.abs(out["m_init"][n] - approx.max(1)).max() < 1e-13
+
+
+# ------------------------------------------------------------------ exactness identity
+CASES = [
+    dict(N=96, d=8, bm=16, bn=16, causal=True, n_sink=1, n_local=1),
+    dict(N=96, d=8, bm=16, bn=16, causal=False, n_sink=1, n_local=1),
+    dict(N=100, d=5, bm=32, bn=8, causal=True, n_sink=2, n_local=2),     # ragged, B_r > B_c
+    dict(N=100, d=5, bm=8, bn=32, causal=True, n_sink=1, n_local=1),     # B_r < B_c
+    dict(N=77, d=16, bm=16, bn=16, causal=False, n_sink=0, n_local=3),
+    dict(N=64, d=4, bm=64, bn=8, causal=True, n_sink=3, n_local=0),
+]
+
+
+@pytest.mark.parametrize("c", CASES)
+@pytest.mark.parametrize("g", [1, 2])
+def test_vfa_equals_exact_for_any_seeded_max(oracle, c, g):
+    """m cancels between O and l, so Alg. 1 gives exact attention whatever value the max was
+    seeded with; in particular whenever the seed bounds the true row max."""
+    B, Hkv = 2, 2
+    Hq = Hkv * g
+    N, d, bm, bn = c["N"], c["d"], c["bm"], c["bn"]
+    Q, K, V = rnd(14, B, Hq, N, d), rnd(15, B, Hkv, N, d), rnd(16, B, Hkv, N, d)
+    K[:, :, 0] *= 3.0
+    blocks = np.array([(b, h, i) for b in range(B) for h in range(Hq) for i in range(-(-N // bm))], np.int32)
+    Oe, Le, Me = oracle.exact(Q, K, V, bm, c["causal"], blocks)
+    valid = ~np.isnan(Le)
+    kw = dict(n_sink=c["n_sink"], n_local=c["n_local"])
+    # (a) the method's own m-init
+    out = oracle.blocks(Q, K, V, bm, bn, c["causal"], blocks, **kw)
+    assert np.abs(out["O"][valid] - Oe[valid]).max() < 1e-12
+    assert np.abs(out["LSE"][valid] - Le[valid]).max() < 1e-12
+    # (b) arbitrary seeds in [M-30, M+30]
+    junk = np.where(valid, Me, 0.0) + np.random.default_rng(5).uniform(-30, 30, Me.shape)
+    out = oracle.blocks(Q, K, V, bm, bn, c["causal"], blocks, m_override=junk, **kw)
+    assert np.abs(out["O"][valid] - Oe[valid]).max() < 1e-10
+    assert np.abs(out["LSE"][valid] - Le[valid]).max() < 1e-10
+    # (c) seeds that bound the true max: every exponent is <= 0 and the frozen m stays the seed
+    bound = np.where(valid, Me, 0.0) + 1.5
+    out = oracle.blocks(Q, K, V, bm, bn, c["causal"], blocks, m_override=bound, **kw)
+    assert np.abs(out["O"][valid] - Oe[valid]).max() < 1e-12
+    assert np.array_equal(out["m_final"][valid], bound[valid])
+    # (d) no m-init at all (allowed when a special block exists)
+    if c["n_sink"] + c["n_local"] > 0:
+        out = oracle.blocks(Q, K, V, bm, bn, c["causal"], blocks, use_minit=False, **kw)
+        assert np.abs(out["O"][valid] - Oe[valid]).max() < 1e-10
+
+
+def test_causal_rows_ignore_future_keys(oracle):
+    B, H, N, d, bm, bn = 1, 1, 64, 8, 16, 16
+    Q, K, V = rnd(17, B, H, N, d), rnd(18, B, H, N, d), rnd(19, B, H, N, d)
+    blocks = np.array([(0, 0, 1)], np.int32)                     # rows 16..31
+    a = oracle.blocks(Q, K, V, bm, bn, True, blocks)
+    K2, V2 = K.copy(), V.copy()
+    K2[:, :, 32:] = 100.0
+    V2[:, :, 32:] = -7.0
+    b = oracle.blocks(Q, K2, V2, bm, bn, True, blocks)
+    assert np.array_equal(a["O"], b["O"]) and np.array_equal(a["LSE"], b["LSE"])
+    # keys inside the diagonal block but after the row are masked too
+    K3 = K.copy(); K3[:, :, 31] = 50.0
+    c = oracle.blocks(Q, K3, V, bm, bn, True, blocks)
+    # (the block summary, hence m_init, sees key 31, so agreement is to rounding, not bitwise)
+    assert np.abs(a["O"][0, :15] - c["O"][0, :15]).max() < 1e-13 and np.abs(a["O"][0, 15] - c["O"][0, 15]).max() > 1e-3
+    a0 = oracle.blocks(Q, K, V, bm, bn, True, blocks, use_minit=False)
+    c0 = oracle.blocks(Q, K3, V, bm, bn, True, blocks, use_minit=False)
+    assert np.array_equal(a0["O"][0, :15], c0["O"][0, :15])
+
+
+# ------------------------------------------------------------------ online-softmax state, step by step
+def test_fa_trajectory_is_running_max_and_sum(oracle):
+    """FA column of Table 1 = online softmax: after k blocks m is the max and l the sum of
+    exp(s - m) over the keys seen so far (definitions, evaluated on the whole score matrix)."""
+    N, d, bm, bn = 80, 6, 16, 16
+    Q, K, V = rnd(20, 1, 1, N, d), rnd(21, 1, 1, N, d), rnd(22, 1, 1, N, d)
+    blocks = np.array([(0, 0, i) for i in range(N // bm)], np.int32)
+    for causal in (False, True):
+        out = oracle.fa2(Q, K, V, bm, bn, causal, blocks, want_traj=True)
+        _, _, _, S = lib_attention(Q[0, 0], K[0, 0], V[0, 0], causal, 1 / math.sqrt(d))
+        for n, (_, _, i) in enumerate(blocks):
+            nvis = (i + 1) if causal else N // bn
+            for k in range(nvis):
+                seen = S[i * bm:(i + 1) * bm, : (k + 1) * bn]
+                m = seen.max(1)
+                l = np.exp(seen - m[:, None]).sum(1)
+                assert np.abs(out["traj"][n, k, :, 0] - m).max() < 1e-14
+                assert np.abs(out["traj"][n, k, :, 1] - l).max() < 1e-12
+        # same switches spelled out on the VFA entry: all blocks special, ascending, no m-init
+        same = oracle.blocks(Q, K, V, bm, bn, causal, blocks, n_sink=0, n_local=0, use_minit=False,
+                             reorder=False, freeze=False)
+        assert np.array_equal(same["O"], out["O"])
+
+
+def test_vfa_trajectory_freezes_after_special_blocks(oracle):
+    N, d, bm, bn = 96, 6, 16, 16
+    Q, K, V = rnd(23, 1, 1, N, d), rnd(24, 1, 1, N, d), rnd(25, 1, 1, N, d)
+    blocks = np.array([(0, 0, 4)], np.int32)
+    out = oracle.blocks(Q, K, V, bm, bn, False, blocks, want_traj=True)
+    _, _, _, S = lib_attention(Q[0, 0], K[0, 0], V[0, 0], False, 1 / math.sqrt(d))
+    rows = S[4 * bm:5 * bm]
+    m_after_special = np.maximum(out["m_init"][0], np.maximum(rows[:, 0:16].max(1), rows[:, 64:80].max(1)))
+    order = [0, 4, 1, 2, 3, 5]
+    seen = []
+    for k, j in enumerate(order):
+        seen.append(rows[:, j * bn:(j + 1) * bn])
+        if k >= 1:
+            assert np.array_equal(out["traj"][0, k, :, 0], m_after_special)          # frozen
+            l = np.exp(np.concatenate(seen, 1) - m_after_special[:, None]).sum(1)    # no rescale factor needed
+            assert np.abs(out["traj"][0, k, :, 1] - l).max() < 1e-11
+
+
+def test_table1_op_counts(oracle):
+    """Table 1: FA runs rowmax and the rescale on every tile; VFA only on the special tiles."""
+    N, d, bm, bn = 128, 4, 16, 16
+    Q, K, V = rnd(26, 1, 1, N, d), rnd(27, 1, 1, N, d), rnd(28, 1, 1, N, d)
+    blocks = np.array([(0, 0, i) for i in range(N // bm)], np.int32)
+    fa = oracle.fa2(Q, K, V, bm, bn, True, blocks)["counters"]
+    vfa = oracle.blocks(Q, K, V, bm, bn, True, blocks)["counters"]
+    for i in range(N // bm):
+        assert fa[i, 0] == fa[i, 1] == fa[i, 2] == i + 1
+        assert vfa[i, 0] == i + 1 and vfa[i, 1] == vfa[i, 2] == min(2, i + 1)
+    vfa = oracle.blocks(Q, K, V, bm, bn, False, blocks, n_sink=2, n_local=3)["counters"]
+    for i in range(N // bm):
+        n_special = len(set(range(2)) | set(range(max(0, i - 2), i + 1)))
+        assert vfa[i, 0] == N // bn and vfa[i, 1] == vfa[i, 2] == n_special
+
+
+# ------------------------------------------------------------------ VSA
+def _vsa_problem(seed=30, N=256, d=8, causal=True):
+    w = wl.small(wl.CONFIGS["cfg2"], B=1, Hq=2, Hkv=1, N=N, d=d, block_m=32, block_n=16, F=1, W=16.0, theta=4.0,
+                 beta=6.0, kappa=3.0)
+    t = wl.generate(w, seed)
+    Q, K, V = (wl.bf16_bits_to_f32(t[k]) for k in "QKV")
+    return w, Q, K, V
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_vsa_no_skip_limit_equals_vfa(oracle, causal):
+    w, Q, K, V = _vsa_problem(causal=causal)
+    blocks = wl.all_blocks(w)
+    a = oracle.blocks(Q, K, V, 32, 16, causal, blocks)
+    b = oracle.blocks(Q, K, V, 32, 16, causal, blocks, vsa=True, skip_threshold_nats=1e4)   # lambda -> 0
+    assert np.array_equal(a["O"], b["O"]) and np.array_equal(a["LSE"], b["LSE"])
+    assert not (b["mask"] == 1).any()
+    for n, (_, _, i) in enumerate(blocks):
+        j_hi = ((i + 1) * 32 - 1) // 16 if causal else w.N // 16 - 1
+        assert np.all(b["mask"][n, : j_hi + 1] == 0) and np.all(b["mask"][n, j_hi + 1:] == 2)
+        assert b["counters"][n, 1] == j_hi + 1              # rowmax on every visited tile in Alg. 2
+
+
+@pytest.mark.parametrize("thr", [2.0, 5.0, 7.0])
+def test_vsa_is_exact_attention_over_kept_tiles_and_loss_is_bounded(oracle, thr):
+    w, Q, K, V = _vsa_problem()
+    blocks = wl.all_blocks(w)
+    out = oracle.blocks(Q, K, V, 32, 16, True, blocks, vsa=True, skip_threshold_nats=thr)
+    Oe, Le, Me = oracle.exact(Q, K, V, 32, True, blocks)
+    lam = math.exp(-thr)
+    assert (out["mask"] == 1).sum() > 0
+    skipped_frac = (out["mask"] == 1).sum() / (out["mask"] != 2).sum()
+    assert out["counters"][:, 3].sum() == (out["mask"] == 1).sum()
+    for n, (b, h, i) in enumerate(blocks):
+        _, _, _, S = lib_attention(Q[b, h], K[b, 0], V[b, 0], True, w.scale)
+        rows = S[i * 32:(i + 1) * 32]
+        keep = np.repeat(out["mask"][n] == 0, 16)
+        Sk = np.where(keep[None, :], rows, -np.inf)
+        # (1) O, LSE = softmax restricted to the kept tiles (the frozen m cancels)
+        P = scipy.special.softmax(Sk, axis=1)
+        assert np.abs(out["O"][n] - P @ V[b, 0].astype(np.float64)).max() < 1e-12
+        assert np.abs(out["LSE"][n] - scipy.special.logsumexp(Sk, axis=1)).max() < 1e-12
+        # (2) every skipped score lies more than thr below the max in use => bounded lost mass
+        skip_keys = np.repeat(out["mask"][n] == 1, 16)
+        if skip_keys.any():
+            smax = np.where(skip_keys[None, :], rows, -np.inf).max(1)
+            assert np.all(smax < out["m_final"][n] - thr)
+        delta = np.minimum(1.0, skip_keys.sum() * lam * np.exp(out["m_final"][n] - Le[n]))
+        assert np.all(np.abs(out["O"][n] - Oe[n]).max(1) <= 2 * delta * np.abs(V).max() + 1e-12)
+        assert np.all(Le[n] - out["LSE"][n] >= -1e-12)
+        # (3) margin sign is the decision
+        vis = out["mask"][n] != 2
+        assert np.array_equal(out["margin"][n][vis] < 0, out["mask"][n][vis] == 1)
+    assert 0.01 < skipped_frac < 0.98
+
+
+def test_blasst_vanilla_mask_from_score_matrix(oracle):
+    """All blocks special, ascending order, no m-init: the running max before block j is the
+    true max over the earlier keys, so the mask follows from the score matrix alone."""
+    w, Q, K, V = _vsa_problem(seed=31, causal=False)
+    thr = 3.0
+    blocks = wl.all_blocks(w)
+    out = oracle.blocks(Q, K, V, 32, 16, False, blocks, n_sink=0, n_local=0, use_minit=False, reorder=False,
+                        freeze=False, vsa=True, skip_threshold_nats=thr)
+    for n, (b, h, i) in enumerate(blocks):
+        _, _, _, S = lib_attention(Q[b, h], K[b, 0], V[b, 0], False, w.scale)
+        tile_max = S[i * 32:(i + 1) * 32].reshape(32, -1, 16).max(2)              # [rows, Tc]
+        run = np.maximum.accumulate(tile_max, axis=1)
+        prev = np.concatenate([np.full((32, 1), -np.inf), run[:, :-1]], 1)
+        want = np.all(tile_max - np.maximum(prev, tile_max) < -thr, axis=0)
+        assert np.array_equal(out["mask"][n] == 1, want)
+    assert (out["mask"] == 1).any() and (out["mask"] == 0).any()
+
+
+def test_vsa_mask_uses_frozen_max(oracle):
+    """Alg. 2 with freeze: on non-special tiles the test compares against
+    m = max(m_init, rowmax of the special tiles that were kept)."""
+    w, Q, K, V = _vsa_problem(seed=32, causal=False)
+    thr = 4.0
+    blocks = wl.all_blocks(w)
+    out = oracle.blocks(Q, K, V, 32, 16, False, blocks, vsa=True, skip_threshold_nats=thr)
+    for n, (b, h, i) in enumerate(blocks):
+        _, _, _, S = lib_attention(Q[b, h], K[b, 0], V[b, 0], False, w.scale)
+        tile_max = S[i * 32:(i + 1) * 32].reshape(32, -1, 16).max(2)
+        m = out["m_init"][n].copy()
+        special = [0] + [j for j in (2 * i, 2 * i + 1) if j != 0]
+        for j in special:
+            skip = np.all(tile_max[:, j] - np.maximum(m, tile_max[:, j]) < -thr)
+            assert (out["mask"][n, j] == 1) == skip
+            if not skip:
+                m = np.maximum(m, tile_max[:, j])
+        assert np.array_equal(m, out["m_final"][n])
+        for j in range(w.N // 16):
+            if j not in special:
+                assert (out["mask"][n, j] == 1) == bool(np.all(tile_max[:, j] < m - thr))
+
+
+def test_all_blocks_skipped_gives_zero_row(oracle):
+    w, Q, K, V = _vsa_problem(seed=33)
+    blocks = wl.all_blocks(w)[:2]
+    huge = np.full((2, 32), 1e3)
+    out = oracle.blocks(Q, K, V, 32, 16, True, blocks, vsa=True, skip_threshold_nats=8.0, m_override=huge)
+    assert np.all(out["O"] == 0) and np.all(np.isneginf(out["LSE"]))
+    assert np.all(out["mask"][out["mask"] != 2] == 1)
+
+
+# ------------------------------------------------------------------ generators
+def test_generators_are_seeded_and_structured(oracle):
+    w = wl.small(wl.CONFIGS["cfg2"], Hq=2, Hkv=1, N=1024)
+    a, b = wl.generate(w, 7), wl.generate(w, 7)
+    assert all(np.array_equal(a[k], b[k]) for k in "QKV")
+    assert not np.array_equal(a["Q"], wl.generate(w, 8)["Q"])
+    Q, K, V = (wl.bf16_bits_to_f32(a[k]) for k in "QKV")
+    assert np.array_equal(wl.f32_to_bf16_bits(Q), a["Q"])                          # round trip is exact
+    blocks = np.array([(0, 0, 7), (0, 1, 5)], np.int32)
+    P, _, _, S = lib_attention(Q[0, 0], K[0, 0], V[0, 0], True, w.scale)
+    # sink: key 0 takes a large share; local: the diagonal band beats the far background
+    assert P[512:, 0].mean() > 0.3
+    near = np.mean([S[r, r - 8:r + 1].mean() for r in range(600, 1000)])
+    far = np.mean([S[r, 100:r - 400].mean() for r in range(600, 1000)])
+    assert near > far + 2.0
+    # planted maxima (m-init stress): the planted key is the row argmax outside sink/local blocks
+    w4 = wl.small(wl.CONFIGS["cfg4"], Hq=1, Hkv=1, N=2048)
+    t = wl.generate(w4, 3)
+    Q, K = wl.bf16_bits_to_f32(t["Q"])[0, 0], wl.bf16_bits_to_f32(t["K"])[0, 0]
+    S = (Q.astype(np.float64) @ K.astype(np.float64).T) * w4.scale
+    arg = S.argmax(1)
+    blk = arg // w4.block_n
+    own = (np.arange(2048) // w4.block_m)[:, None] * 2 + np.arange(2)[None, :]
+    middle = (blk >= w4.n_sink) & ~(blk[:, None] == own).any(1)
+    assert middle.mean() > 0.95 and np.median(S.max(1)) > 5.0
+
+
+def test_bf16_rounding_is_nearest_even():
+    x = np.array([1.0, 1.00390625, 1.01171875, -1.00390625, 3.4e38, 1e-40, 0.0], np.float32)
+    bits = wl.f32_to_bf16_bits(x)
+    back = wl.bf16_bits_to_f32(bits)
+    # 1 + 2^-8 is a tie -> even (1.0); 1 + 3*2^-8 is a tie -> even (1 + 2^-6)
+    assert back[0] == 1.0 and back[1] == 1.0 and back[2] == 1.015625 and back[3] == -1.0
+    assert np.isinf(back[4]) and back[6] == 0.0
+    import torch
+    y = np.random.default_rng(0).standard_normal(10000).astype(np.float32) * 37
+    t = torch.from_numpy(y).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(wl.f32_to_bf16_bits(y), t)
