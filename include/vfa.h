@@ -1,0 +1,90 @@
+/*
+ * vfa.h -- C ABI of libvfa.so: the VFA / VSA attention forward path for AMD MI355X (gfx950).
+ *
+ * Every pointer is a DEVICE pointer owned by the caller.  The library allocates nothing,
+ * frees nothing and keeps no state between calls.  Calls are asynchronous: they enqueue
+ * kernels on `stream` (a hipStream_t passed as void*, NULL = the default stream) and return;
+ * the caller keeps every buffer alive until the stream has passed the call.
+ *
+ * Tensor layouts (row-major, last index contiguous, 16-byte aligned base pointers):
+ *   Q, O   [B, Hq,  N, d]  bf16
+ *   K, V   [B, Hkv, N, d]  bf16       query head h reads KV head h / (Hq / Hkv)
+ *   LSE    [B, Hq, N]      fp32       natural-log sum of exp of the scaled scores; may be NULL
+ *   Krepr  [B, Hkv, ceil(N / block_n), d] bf16   key-block summaries (lives in `workspace`)
+ *   skip_mask [B, Hq, ceil(N / block_m), ceil(N / block_n)] uint8; may be NULL
+ *            0 = tile computed, 1 = tile skipped by the threshold test, 2 = tile not visited
+ *
+ * Supported shapes: d in {64, 128}; (block_m, block_n) in {(64, 64), (128, 64)}; any N >= 0
+ * (ragged tails are masked); Hq a multiple of Hkv.  B == 0 or N == 0 is a successful no-op.
+ * softmax_scale <= 0 selects 1 / sqrt(d).
+ *
+ * Return value: VFA_OK, or a negative code; vfa_strerror() names it.  Nothing is launched
+ * when a negative code is returned, except VFA_ERR_HIP (a launch itself failed).
+ * The functions never throw, abort or print.  Same inputs give bit-identical outputs.
+ */
+#ifndef VFA_H_
+#define VFA_H_
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VFA_OK 0
+#define VFA_ERR_INVALID_ARG (-1) /* null/misaligned pointer, negative size, Hq % Hkv != 0, bad flag combination, workspace too small */
+#define VFA_ERR_UNSUPPORTED (-2) /* d or block sizes outside the compiled set, sizes beyond 32-bit grid limits */
+#define VFA_ERR_HIP (-3)         /* the HIP runtime reported a launch error */
+
+/* Bytes of `workspace` that vfa_attn_fwd / vsa_attn_fwd need (the Krepr tensor, rounded up
+ * to 256 bytes).  Returns 0 for invalid arguments. */
+size_t vfa_workspace_bytes(int B, int Hkv, int N, int d, int block_n);
+
+/* Key-block summary pre-pass (Alg. 1, "precompute key-block representations"; Methods, Step 1):
+ * Krepr[b, h, j, t] = the element of K[b, h, j*block_n : (j+1)*block_n, t] with the largest
+ * absolute value, sign kept; when +a and -a tie, +a.  The result is an element of K, so bf16
+ * is exact.  vfa_attn_fwd / vsa_attn_fwd run this themselves; it is exported for callers that
+ * keep summaries across calls (a growing KV cache appends blocks). */
+int vfa_kblock_summary(const void* K, void* Krepr, int B, int Hkv, int N, int d, int block_n,
+                       void* stream);
+
+/* Conventional online-softmax forward (Table 1, FA column; Sec. 2.2 "Flash Attention"): key
+ * blocks in ascending order, row max / rescale on every block.  The A/B comparison kernel. */
+int fa_baseline_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
+                    int Hq, int Hkv, int N, int d, int block_m, int block_n, int causal,
+                    float softmax_scale, void* stream);
+
+/* VFA forward (Alg. 1).  For each query block: the running max starts at
+ * m_init = max_j scale * Q_i . Krepr_j over the visible key blocks (use_minit = 1: the summaries
+ * are computed into `workspace` first; use_minit = 2: `workspace` already holds them, e.g. from
+ * vfa_kblock_summary on an earlier call; use_minit = 0: the max starts at -inf).  Key blocks
+ * are visited as: the first n_sink blocks, then the local blocks (those overlapping the query
+ * block's own token range plus the n_local-1 blocks before them; none if n_local == 0), then
+ * all remaining visible blocks in ascending order, each block once.  Sink and
+ * local blocks take the exact online-softmax update; all others reuse the frozen max (no row
+ * max, no rescale).  O = acc / l, LSE = m + ln l.  Mathematically equal to exact attention.
+ * use_minit == 0 with n_sink + n_local == 0 is rejected (the max would stay -inf).
+ * `workspace` must hold vfa_workspace_bytes(...) bytes when use_minit != 0; use_minit = 1
+ * overwrites it. */
+int vfa_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq,
+                 int Hkv, int N, int d, int block_m, int block_n, int causal, int n_sink,
+                 int n_local, int use_minit, float softmax_scale, void* workspace,
+                 size_t workspace_bytes, void* stream);
+
+/* VSA forward (Alg. 2) = VFA plus the BLASST-style test on every visited tile: with
+ * m~ = rowmax(S_ij) and m = the running max, the tile is skipped (no exp, no V load, no P.V)
+ * iff m~ - max(m, m~) < -skip_threshold_nats for ALL rows of the query block
+ * (skip_threshold_nats = -ln(lambda) > 0).  A skipped tile changes no state.  Rows whose
+ * tiles were all skipped give O = 0, LSE = -inf. */
+int vsa_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq,
+                 int Hkv, int N, int d, int block_m, int block_n, int causal, int n_sink,
+                 int n_local, int use_minit, float softmax_scale, float skip_threshold_nats,
+                 unsigned char* skip_mask, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Static string for a return code. */
+const char* vfa_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VFA_H_ */

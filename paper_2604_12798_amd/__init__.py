@@ -1,0 +1,149 @@
+"""Thin Python binding of libvfa.so (the C ABI declared in include/vfa.h).
+
+Argument marshalling only: every step of the attention path runs in the HIP kernels behind
+the C entry points.  torch is used for device memory and streams.  There is no fallback: if
+the library is missing, or a call returns an error code, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libvfa.so")
+_lib = None
+
+EXPORTS = ("vfa_workspace_bytes", "vfa_kblock_summary", "fa_baseline_fwd", "vfa_attn_fwd", "vsa_attn_fwd",
+           "vfa_strerror")
+
+
+class VfaError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {strerror(code)} (code {code})")
+        self.code = code
+
+
+def lib() -> ctypes.CDLL:
+    """Load libvfa.so (built in-tree by build.py / __graft_entry__.build()); never falls back."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2604_12798_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+        L.vfa_workspace_bytes.restype = sz
+        L.vfa_workspace_bytes.argtypes = [i, i, i, i, i]
+        L.vfa_kblock_summary.restype = i
+        L.vfa_kblock_summary.argtypes = [vp, vp, i, i, i, i, i, vp]
+        L.fa_baseline_fwd.restype = i
+        L.fa_baseline_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, f, vp]
+        L.vfa_attn_fwd.restype = i
+        L.vfa_attn_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, i, i, f, vp, sz, vp]
+        L.vsa_attn_fwd.restype = i
+        L.vsa_attn_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, i, i, f, f, vp, vp, sz, vp]
+        L.vfa_strerror.restype = ctypes.c_char_p
+        L.vfa_strerror.argtypes = [i]
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().vfa_strerror(int(code)).decode()
+
+
+def workspace_bytes(B: int, Hkv: int, N: int, d: int, block_n: int) -> int:
+    return int(lib().vfa_workspace_bytes(B, Hkv, N, d, block_n))
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _check_qkv(Q, K, V):
+    import torch
+    for t in (Q, K, V):
+        if not (t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.dim() == 4):
+            raise ValueError("Q, K, V must be contiguous 4-d bf16 tensors on the GPU")
+    B, Hq, N, d = Q.shape
+    if K.shape != V.shape or K.shape[0] != B or K.shape[2] != N or K.shape[3] != d:
+        raise ValueError("K, V must be [B, Hkv, N, d] matching Q [B, Hq, N, d]")
+    return B, Hq, K.shape[1], N, d
+
+
+def _outputs(Q, out, lse, want_lse):
+    import torch
+    B, Hq, N, d = Q.shape
+    O = torch.empty_like(Q) if out is None else out
+    L = lse
+    if L is None and want_lse:
+        L = torch.empty((B, Hq, N), dtype=torch.float32, device=Q.device)
+    return O, L
+
+
+def kblock_summary(K, block_n: int = 64, out=None, stream=None):
+    """Key-block summaries Krepr [B, Hkv, ceil(N/block_n), d] (bf16) of K [B, Hkv, N, d]."""
+    import torch
+    B, Hkv, N, d = K.shape
+    Tc = -(-N // block_n)
+    R = torch.empty((B, Hkv, Tc, d), dtype=torch.bfloat16, device=K.device) if out is None else out
+    rc = lib().vfa_kblock_summary(_ptr(K), _ptr(R), B, Hkv, N, d, block_n, _stream(stream))
+    if rc != 0:
+        raise VfaError(rc, "vfa_kblock_summary")
+    return R
+
+
+def fa_baseline_fwd(Q, K, V, *, block_m=128, block_n=64, causal=True, softmax_scale=0.0, out=None, lse=None,
+                    want_lse=True, stream=None):
+    B, Hq, Hkv, N, d = _check_qkv(Q, K, V)
+    O, L = _outputs(Q, out, lse, want_lse)
+    rc = lib().fa_baseline_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(L), B, Hq, Hkv, N, d, block_m, block_n,
+                               int(bool(causal)), float(softmax_scale), _stream(stream))
+    if rc != 0:
+        raise VfaError(rc, "fa_baseline_fwd")
+    return O, L
+
+
+def _workspace(Q, K, block_n, workspace):
+    import torch
+    B, Hkv, N, d = K.shape
+    need = workspace_bytes(B, Hkv, N, d, block_n)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=Q.device)
+    return workspace, workspace.numel() * workspace.element_size()
+
+
+def vfa_attn_fwd(Q, K, V, *, block_m=128, block_n=64, causal=True, n_sink=1, n_local=1, use_minit=True,
+                 softmax_scale=0.0, workspace=None, out=None, lse=None, want_lse=True, stream=None):
+    B, Hq, Hkv, N, d = _check_qkv(Q, K, V)
+    O, L = _outputs(Q, out, lse, want_lse)
+    ws, ws_bytes = _workspace(Q, K, block_n, workspace)
+    rc = lib().vfa_attn_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(L), B, Hq, Hkv, N, d, block_m, block_n,
+                            int(bool(causal)), int(n_sink), int(n_local), int(use_minit), float(softmax_scale),
+                            _ptr(ws), ws_bytes, _stream(stream))
+    if rc != 0:
+        raise VfaError(rc, "vfa_attn_fwd")
+    return O, L
+
+
+def vsa_attn_fwd(Q, K, V, *, block_m=128, block_n=64, causal=True, n_sink=1, n_local=1, use_minit=True,
+                 softmax_scale=0.0, skip_threshold_nats=8.0, skip_mask=None, want_mask=True, workspace=None,
+                 out=None, lse=None, want_lse=True, stream=None):
+    import torch
+    B, Hq, Hkv, N, d = _check_qkv(Q, K, V)
+    O, L = _outputs(Q, out, lse, want_lse)
+    ws, ws_bytes = _workspace(Q, K, block_n, workspace)
+    M = skip_mask
+    if M is None and want_mask:
+        M = torch.empty((B, Hq, -(-N // block_m), -(-N // block_n)), dtype=torch.uint8, device=Q.device)
+    rc = lib().vsa_attn_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(L), B, Hq, Hkv, N, d, block_m, block_n,
+                            int(bool(causal)), int(n_sink), int(n_local), int(use_minit), float(softmax_scale),
+                            float(skip_threshold_nats), _ptr(M), _ptr(ws), ws_bytes, _stream(stream))
+    if rc != 0:
+        raise VfaError(rc, "vsa_attn_fwd")
+    return O, L, M

@@ -1,0 +1,567 @@
+// VFA / VSA / online-softmax attention forward for gfx950 (MI355X), and the C ABI around it.
+//
+// One workgroup owns one query block (block_m rows of one head); each of its NW = block_m / 32
+// waves owns 32 query rows.  Key/value tiles of 64 keys stream through LDS.  Scores are
+// computed TRANSPOSED, S^T = K_j Q_i^T, with v_mfma_f32_32x32x16_bf16: in the accumulator
+// layout every lane then holds 32 scores of ONE query (lane & 31), so the softmax row
+// statistics are in-lane plus one exchange with lane ^ 32, the rescale factor is a per-lane
+// scalar, and exp(S^T) converted to bf16 is already laid out as the B operand of
+// O^T += V_j^T P^T.  V_j^T fragments come from the row-major V tile in LDS through the
+// transposing read ds_read_b64_tr_b16.
+//
+// Softmax runs in the log2 domain: p = exp2(s * c - m2) with c = scale * log2(e) and m2 = c * (row
+// max of the raw scores); LSE = (m2 + log2 l) * ln 2.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <math.h>
+
+#include "vfa.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr int BN = 64;  // keys per tile (= block_n)
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+enum Mode { MODE_FA = 0, MODE_VFA = 1, MODE_VSA = 2 };
+
+struct Params {
+    const uint16_t* Q;
+    const uint16_t* K;
+    const uint16_t* V;
+    const uint16_t* Krepr;
+    uint16_t* O;
+    float* LSE;
+    uint8_t* mask;
+    int B, Hq, Hkv, N, Tr, Tc;
+    int causal, n_sink, n_local, use_minit;
+    float c;     // softmax scale * log2(e)
+    float thr2;  // skip threshold in log2 units
+};
+
+// ---------------------------------------------------------------------------------------------
+// LDS tile layout.  A tile is 64 rows of D bf16 (ROWB = 2*D bytes, CH = ROWB/16 16-byte chunks).
+// K tiles are read with ds_read_b128, 32 consecutive rows at one chunk column per half wave:
+// chunk' = chunk ^ (row & (CH-1)) spreads 16 consecutive rows over all 64 banks.
+// V tiles are read with ds_read_b64_tr_b16, 4 consecutive rows x 64 contiguous bytes per half
+// wave: the 64-byte window index is XORed with (row & 3) so the 4 rows use distinct banks.
+template <int D>
+struct Tile {
+    static constexpr int ROWB = 2 * D;
+    static constexpr int CH = ROWB / 16;
+    static constexpr int BYTES = BN * ROWB;
+    __device__ static int k_off(int row, int chunk) { return row * ROWB + ((chunk ^ (row & (CH - 1))) << 4); }
+    __device__ static int v_off(int row, int chunk) { return row * ROWB + ((chunk ^ ((row & (CH / 4 - 1)) << 2)) << 4); }
+};
+
+__device__ inline float xhalf_max(float x) {
+    // max of x over the lane pair (l, l ^ 32)
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ inline float xhalf_sum(float x) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+__device__ inline uint32_t pack_bf16(float a, float b) {
+    f32x2 v = {a, b};
+    bf16x2 r = __builtin_convertvector(v, bf16x2);  // v_cvt_pk_bf16_f32, round to nearest even
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Visit order of one query block: [0, n1) sink tiles, [s2, s2 + n2) local tiles, then the
+// remaining visible tiles ascending.  The first n_special visits take the exact-max update.
+struct Visit {
+    int n1, s2, n2, total, n_special;
+    __device__ int tile(int k) const {
+        if (k < n1) return k;
+        k -= n1;
+        if (k < n2) return s2 + k;
+        k -= n2;
+        int j = n1 + k;
+        if (n2 > 0 && j >= s2) j += n2;
+        return j;
+    }
+};
+
+template <int D, int NW, int MODE>
+__global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const Params p) {
+    using T = Tile<D>;
+    constexpr int BM = 32 * NW;
+    constexpr int NT = 64 * NW;
+    constexpr int KK = D / 16;                 // k-steps of Q K^T
+    constexpr int DB = D / 32;                 // 32-row blocks of O^T
+    constexpr int LD = (BN * T::CH) / NT;      // 16-byte chunks each thread moves per tile
+
+    __shared__ __attribute__((aligned(16))) uint8_t smem[4 * T::BYTES];  // K[2], V[2]
+    __shared__ int votes[2][NW];
+    uint8_t* const Ks = smem;
+    uint8_t* const Vs = smem + 2 * T::BYTES;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int ql = lane & 31;  // query column inside the wave
+    const int hh = lane >> 5;  // which half of the k / row split this lane holds
+
+    // ---- workgroup -> (b, h, i): heavy (late) query blocks first; all query heads of one KV
+    // head, and the KV heads congruent mod 8, stay on one XCD (workgroup ids go round-robin
+    // over the 8 XCDs) so their K/V tiles share that XCD's L2.
+    const int g = p.Hq / p.Hkv;
+    const int G = p.B * p.Hkv;
+    int b, h, i;
+    {
+        const int id = blockIdx.x;
+        if ((G & 7) == 0) {
+            const int x = id & 7, y = id >> 3;
+            const int per = p.Tr * g;
+            const int kvl = y / per, rem = y - kvl * per;
+            i = p.Tr - 1 - rem / g;
+            const int kv = kvl * 8 + x;
+            b = kv / p.Hkv;
+            h = (kv - b * p.Hkv) * g + rem % g;
+        } else {
+            const int bh = id % (p.B * p.Hq);
+            i = p.Tr - 1 - id / (p.B * p.Hq);
+            b = bh / p.Hq;
+            h = bh - b * p.Hq;
+        }
+    }
+    const int hkv = h / g;
+    const int N = p.N;
+    const int row0 = i * BM;
+    const int last_row = min(N, row0 + BM) - 1;
+    const int a_lo = row0 / BN, a_hi = last_row / BN;
+    const int j_hi = p.causal ? a_hi : p.Tc - 1;
+
+    const uint16_t* Qg = p.Q + ((size_t)(b * p.Hq + h) * N) * D;
+    const uint16_t* Kg = p.K + ((size_t)(b * p.Hkv + hkv) * N) * D;
+    const uint16_t* Vg = p.V + ((size_t)(b * p.Hkv + hkv) * N) * D;
+
+    // ---- Q fragments: B operand of S^T = K Q^T; lane holds Q[row0 + 32*wave + ql][16*kk + 8*hh .. +7]
+    const int qrow = row0 + 32 * wave + ql;
+    const int qrow_c = min(qrow, N - 1);
+    bf16x8 qf[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk)
+        qf[kk] = *reinterpret_cast<const bf16x8*>(Qg + (size_t)qrow_c * D + 16 * kk + 8 * hh);
+
+    // ---- tile movers: global -> registers -> LDS (swizzled)
+    u32x4 kreg[LD], vreg[LD];
+    auto load_rows = [&](const uint16_t* base, int first_row, int row_limit, u32x4* reg) {
+#pragma unroll
+        for (int u = 0; u < LD; ++u) {
+            const int q = u * NT + tid;
+            const int r = q / T::CH, ch = q % T::CH;
+            const int gr = min(first_row + r, row_limit - 1);
+            reg[u] = *reinterpret_cast<const u32x4*>(base + (size_t)gr * D + ch * 8);
+        }
+    };
+    auto store_k = [&](uint8_t* dst, const u32x4* reg) {
+#pragma unroll
+        for (int u = 0; u < LD; ++u) {
+            const int q = u * NT + tid;
+            *reinterpret_cast<u32x4*>(dst + T::k_off(q / T::CH, q % T::CH)) = reg[u];
+        }
+    };
+    auto store_v = [&](uint8_t* dst, const u32x4* reg) {
+#pragma unroll
+        for (int u = 0; u < LD; ++u) {
+            const int q = u * NT + tid;
+            *reinterpret_cast<u32x4*>(dst + T::v_off(q / T::CH, q % T::CH)) = reg[u];
+        }
+    };
+
+    // S^T tile: st[t][i] = score of query ql against key 32*t + 8*(i/4) + 4*hh + (i%4)
+    auto qk_tile = [&](const uint8_t* kt, f32x16* st) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            st[t] = f32x16{0};
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) {
+                const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kt + T::k_off(32 * t + ql, 2 * kk + hh));
+                st[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], st[t], 0, 0, 0);
+            }
+        }
+    };
+
+    // ---- m-initialisation: m2 = c * max_j Q_i . Krepr_j over visible key blocks (raw scores here)
+    float m2 = -INFINITY;
+    if (MODE != MODE_FA && p.use_minit) {
+        const uint16_t* Rg = p.Krepr + ((size_t)(b * p.Hkv + hkv) * p.Tc) * D;
+        float mx = -INFINITY;
+        const int n_sum_tiles = (j_hi + BN) / BN;
+        for (int ts = 0; ts < n_sum_tiles; ++ts) {
+            load_rows(Rg, ts * BN, p.Tc, kreg);
+            __syncthreads();  // previous tile's readers are done
+            store_k(Ks, kreg);
+            __syncthreads();
+            f32x16 st[2];
+            qk_tile(Ks, st);
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int j = ts * BN + 32 * t + 8 * (r >> 2) + 4 * hh + (r & 3);
+                    mx = fmaxf(mx, j <= j_hi ? st[t][r] : -INFINITY);
+                }
+        }
+        m2 = xhalf_max(mx) * p.c;
+        __syncthreads();
+    }
+
+    // ---- visit order
+    Visit vis;
+    if (MODE == MODE_FA) {
+        vis.n1 = 0; vis.s2 = 0; vis.n2 = 0;
+        vis.total = j_hi + 1;
+        vis.n_special = vis.total;
+    } else {
+        vis.n1 = min(p.n_sink, j_hi + 1);
+        vis.n2 = 0; vis.s2 = 0;
+        if (p.n_local > 0) {
+            const int lo = max(max(0, a_lo - (p.n_local - 1)), vis.n1), hi = min(a_hi, j_hi);
+            if (hi >= lo) { vis.s2 = lo; vis.n2 = hi - lo + 1; }
+        }
+        vis.total = j_hi + 1;
+        vis.n_special = vis.n1 + vis.n2;
+    }
+
+    if (MODE == MODE_VSA && p.mask) {  // tiles this query block never visits
+        uint8_t* mrow = p.mask + ((size_t)(b * p.Hq + h) * p.Tr + i) * p.Tc;
+        for (int j = j_hi + 1 + tid; j < p.Tc; j += NT) mrow[j] = 2;
+    }
+
+    f32x16 ot[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) ot[db] = f32x16{0};
+    float lsum = 0.f;  // this lane's share of l (its 32 of the 64 keys of every tile)
+
+    // one tile: softmax on st, then O^T += V^T P^T
+    auto softmax_pv = [&](f32x16* st, const uint8_t* vt, int j, bool special, bool masked) {
+        if (masked) {
+            const int limit = p.causal ? min(qrow, N - 1) : N - 1;  // last visible key of this query
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = j * BN + 32 * t + 8 * (r >> 2) + 4 * hh + (r & 3);
+                    st[t][r] = key <= limit ? st[t][r] : -INFINITY;
+                }
+        }
+        float msub = m2;
+        if (special) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, st[t][r]);
+            const float m_new = fmaxf(m2, xhalf_max(mx) * p.c);
+            msub = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(m2 - msub);
+            lsum *= alpha;
+#pragma unroll
+            for (int db = 0; db < DB; ++db) ot[db] *= alpha;
+            m2 = m_new;
+        }
+        uint32_t pk[16];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; r += 2) {
+                const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[t][r], p.c, -msub));
+                const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[t][r + 1], p.c, -msub));
+                lsum += p0;
+                lsum += p1;
+                pk[8 * t + (r >> 1)] = pack_bf16(p0, p1);
+            }
+        // P^T fragment of key chunk c (16 keys): registers 8*(c&1) .. +7 of st[c >> 1], in order
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const u32x4 pw = {pk[4 * c], pk[4 * c + 1], pk[4 * c + 2], pk[4 * c + 3]};
+            const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                // V^T fragment: lane gets V[16c + 8u + 4hh + e][32db + (lane & 31)], e = 0..3, u = 0, 1
+                const int s = lane & 15, dsel = (lane >> 4) & 1;
+                const int chunk = 4 * db + 2 * dsel + ((s & 3) >> 1);
+                const int key0 = 16 * c + 4 * hh + (s >> 2);
+                const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) s16x4*)(vt + T::v_off(key0, chunk) + ((s & 1) << 3)));
+                const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) s16x4*)(vt + T::v_off(key0 + 8, chunk) + ((s & 1) << 3)));
+                const u32x2 a0 = __builtin_bit_cast(u32x2, v0), a1 = __builtin_bit_cast(u32x2, v1);
+                const u32x4 aw = {a0[0], a0[1], a1[0], a1[1]};
+                ot[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aw), pf, ot[db], 0, 0, 0);
+            }
+        }
+    };
+
+    // ---- main loop, double-buffered: tile k+1 travels global -> registers while tile k computes
+    {
+        const int j0 = vis.tile(0);
+        load_rows(Kg, j0 * BN, N, kreg);
+        load_rows(Vg, j0 * BN, N, vreg);
+        store_k(Ks, kreg);
+        store_v(Vs, vreg);
+        __syncthreads();
+    }
+    for (int k = 0; k < vis.total; ++k) {
+        const int j = vis.tile(k);
+        const int buf = k & 1;
+        const bool more = k + 1 < vis.total;
+        if (more) {
+            const int jn = vis.tile(k + 1);
+            load_rows(Kg, jn * BN, N, kreg);
+            load_rows(Vg, jn * BN, N, vreg);
+        }
+        const bool special = k < vis.n_special;
+        const bool masked = (p.causal && j * BN + BN - 1 > row0) || (j + 1) * BN > N;
+        f32x16 st[2];
+        qk_tile(Ks + buf * T::BYTES, st);
+        bool keep = true;
+        if (MODE == MODE_VSA) {
+            // block vote: skip iff every row of the query block has m~ < m - threshold
+            const int limit = p.causal ? min(qrow, N - 1) : N - 1;
+            float mx = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = j * BN + 32 * t + 8 * (r >> 2) + 4 * hh + (r & 3);
+                    mx = fmaxf(mx, (!masked || key <= limit) ? st[t][r] : -INFINITY);
+                }
+            const float mt2 = xhalf_max(mx) * p.c;
+            const bool row_keeps = (qrow < N) && (mt2 != -INFINITY) && !(mt2 < m2 - p.thr2);
+            const bool wave_keeps = __builtin_amdgcn_ballot_w64(row_keeps) != 0;
+            if (lane == 0) votes[buf][wave] = wave_keeps ? 1 : 0;
+            __syncthreads();
+            int any = 0;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) any |= votes[buf][w];
+            keep = any != 0;
+            if (p.mask && tid == 0)
+                p.mask[((size_t)(b * p.Hq + h) * p.Tr + i) * p.Tc + j] = keep ? 0 : 1;
+        }
+        if (keep) {
+            const uint8_t* vt = Vs + buf * T::BYTES;
+            if (special) {
+                if (masked) softmax_pv(st, vt, j, true, true);
+                else softmax_pv(st, vt, j, true, false);
+            } else {
+                if (masked) softmax_pv(st, vt, j, false, true);
+                else softmax_pv(st, vt, j, false, false);
+            }
+        }
+        if (more) {
+            store_k(Ks + (buf ^ 1) * T::BYTES, kreg);
+            store_v(Vs + (buf ^ 1) * T::BYTES, vreg);
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue: O = O^T / l, LSE = (m2 + log2 l) ln 2
+    const float l = xhalf_sum(lsum);
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    if (qrow < N) {
+        uint16_t* Og = p.O + ((size_t)(b * p.Hq + h) * N + qrow) * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const u32x2 w = {pack_bf16(ot[db][4 * q4] * inv, ot[db][4 * q4 + 1] * inv),
+                                 pack_bf16(ot[db][4 * q4 + 2] * inv, ot[db][4 * q4 + 3] * inv)};
+                *reinterpret_cast<u32x2*>(Og + 32 * db + 8 * q4 + 4 * hh) = w;
+            }
+        if (p.LSE && hh == 0)
+            p.LSE[(size_t)(b * p.Hq + h) * N + qrow] = l > 0.f ? (m2 + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Key-block summary: one workgroup per (b*Hkv + h, j); signed element of largest magnitude per
+// dimension over the block's keys, ties to the positive value.  Works on bf16 bit patterns:
+// magnitude order = order of (bits & 0x7fff); on equal magnitude the smaller pattern is the
+// positive one.
+__device__ inline uint32_t sabs_pick(uint32_t a, uint32_t b) {  // one bf16 in the low 16 bits
+    const uint32_t ma = a & 0x7fffu, mb = b & 0x7fffu;
+    return ma > mb ? a : (mb > ma ? b : min(a, b));
+}
+__device__ inline uint32_t sabs_pick2(uint32_t a, uint32_t b) {  // two packed bf16
+    return sabs_pick(a & 0xffffu, b & 0xffffu) | (sabs_pick(a >> 16, b >> 16) << 16);
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void kblock_summary_kernel(const uint16_t* __restrict__ K, uint16_t* __restrict__ R,
+                                                             int N, int Tc, int block_n) {
+    constexpr int CH = D / 8;        // 16-byte chunks per row
+    constexpr int RG = 256 / CH;     // row groups
+    __shared__ u32x4 part[RG][CH];
+    const int j = blockIdx.x, bh = blockIdx.y;
+    const int ch = threadIdx.x % CH, rg = threadIdx.x / CH;
+    const int c0 = j * block_n, c1 = min(N, c0 + block_n);
+    const uint16_t* base = K + (size_t)bh * N * D;
+    u32x4 acc = {0, 0, 0, 0};
+    for (int r = c0 + rg; r < c1; r += RG) {
+        const u32x4 x = *reinterpret_cast<const u32x4*>(base + (size_t)r * D + ch * 8);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] = sabs_pick2(acc[e], x[e]);
+    }
+    part[rg][ch] = acc;
+    __syncthreads();
+    if (rg == 0) {
+        for (int q = 1; q < RG; ++q) {
+            const u32x4 x = part[q][ch];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] = sabs_pick2(acc[e], x[e]);
+        }
+        *reinterpret_cast<u32x4*>(R + ((size_t)bh * Tc + j) * D + ch * 8) = acc;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+int check_common(const void* Q, const void* K, const void* V, void* O, const float* LSE, int B, int Hq, int Hkv,
+                 int N, int d, int block_m, int block_n) {
+    if (B < 0 || N < 0 || Hq <= 0 || Hkv <= 0 || d <= 0 || block_m <= 0 || block_n <= 0) return VFA_ERR_INVALID_ARG;
+    if (Hq % Hkv != 0) return VFA_ERR_INVALID_ARG;
+    if (d != 64 && d != 128) return VFA_ERR_UNSUPPORTED;
+    if (!(block_n == 64 && (block_m == 64 || block_m == 128))) return VFA_ERR_UNSUPPORTED;
+    if (B == 0 || N == 0) return VFA_OK;
+    if (!Q || !K || !V || !O) return VFA_ERR_INVALID_ARG;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return VFA_ERR_INVALID_ARG;
+    if (LSE && (reinterpret_cast<uintptr_t>(LSE) & 3u)) return VFA_ERR_INVALID_ARG;
+    const long long wgs = (long long)B * Hq * ceil_div(N, block_m);
+    if (wgs > 0x7fffffffLL || (long long)B * Hq * N > 0x7fffffffLL) return VFA_ERR_UNSUPPORTED;
+    return VFA_OK;
+}
+
+template <int MODE>
+int launch_fwd(const Params& p, int d, int block_m, hipStream_t s) {
+    const dim3 grid((unsigned)(p.B * p.Hq * p.Tr));
+    (void)hipGetLastError();
+    if (d == 128 && block_m == 128) attn_fwd_kernel<128, 4, MODE><<<grid, 256, 0, s>>>(p);
+    else if (d == 128 && block_m == 64) attn_fwd_kernel<128, 2, MODE><<<grid, 128, 0, s>>>(p);
+    else if (d == 64 && block_m == 128) attn_fwd_kernel<64, 4, MODE><<<grid, 256, 0, s>>>(p);
+    else if (d == 64 && block_m == 64) attn_fwd_kernel<64, 2, MODE><<<grid, 128, 0, s>>>(p);
+    else return VFA_ERR_UNSUPPORTED;
+    return hipGetLastError() == hipSuccess ? VFA_OK : VFA_ERR_HIP;
+}
+
+int summary_launch(const void* K, void* Krepr, int B, int Hkv, int N, int d, int block_n, hipStream_t s) {
+    const int Tc = ceil_div(N, block_n);
+    const dim3 grid((unsigned)Tc, (unsigned)(B * Hkv));
+    (void)hipGetLastError();
+    if (d == 128) kblock_summary_kernel<128><<<grid, 256, 0, s>>>((const uint16_t*)K, (uint16_t*)Krepr, N, Tc, block_n);
+    else kblock_summary_kernel<64><<<grid, 256, 0, s>>>((const uint16_t*)K, (uint16_t*)Krepr, N, Tc, block_n);
+    return hipGetLastError() == hipSuccess ? VFA_OK : VFA_ERR_HIP;
+}
+
+int vfa_vsa_common(int mode, const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv,
+                   int N, int d, int block_m, int block_n, int causal, int n_sink, int n_local, int use_minit,
+                   float softmax_scale, float thr_nats, unsigned char* skip_mask, void* workspace,
+                   size_t workspace_bytes, void* stream) {
+    int rc = check_common(Q, K, V, O, LSE, B, Hq, Hkv, N, d, block_m, block_n);
+    if (rc != VFA_OK) return rc;
+    if (n_sink < 0 || n_local < 0) return VFA_ERR_INVALID_ARG;
+    if (!use_minit && n_sink + n_local == 0) return VFA_ERR_INVALID_ARG;
+    if (mode == MODE_VSA && !(thr_nats > 0.f && isfinite(thr_nats))) return VFA_ERR_INVALID_ARG;
+    if (!isfinite(softmax_scale)) return VFA_ERR_INVALID_ARG;
+    if (use_minit < 0 || use_minit > 2) return VFA_ERR_INVALID_ARG;
+    if (B == 0 || N == 0) return VFA_OK;
+    if (use_minit) {
+        if (!workspace || !aligned16(workspace) || workspace_bytes < vfa_workspace_bytes(B, Hkv, N, d, block_n))
+            return VFA_ERR_INVALID_ARG;
+        if ((long long)B * Hkv > 65535) return VFA_ERR_UNSUPPORTED;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    if (use_minit == 1) {
+        rc = summary_launch(K, workspace, B, Hkv, N, d, block_n, s);
+        if (rc != VFA_OK) return rc;
+    }
+    Params p{};
+    p.Q = (const uint16_t*)Q; p.K = (const uint16_t*)K; p.V = (const uint16_t*)V;
+    p.Krepr = (const uint16_t*)workspace; p.O = (uint16_t*)O; p.LSE = LSE; p.mask = skip_mask;
+    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N; p.Tr = ceil_div(N, block_m); p.Tc = ceil_div(N, block_n);
+    p.causal = causal ? 1 : 0; p.n_sink = n_sink; p.n_local = n_local; p.use_minit = use_minit ? 1 : 0;
+    const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)d);
+    p.c = scale * kLog2e;
+    p.thr2 = thr_nats * kLog2e;
+    return mode == MODE_VSA ? launch_fwd<MODE_VSA>(p, d, block_m, s) : launch_fwd<MODE_VFA>(p, d, block_m, s);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t vfa_workspace_bytes(int B, int Hkv, int N, int d, int block_n) {
+    if (B <= 0 || Hkv <= 0 || N <= 0 || d <= 0 || block_n <= 0) return 0;
+    const size_t bytes = (size_t)B * Hkv * ceil_div(N, block_n) * d * 2;
+    return (bytes + 255) & ~(size_t)255;
+}
+
+int vfa_kblock_summary(const void* K, void* Krepr, int B, int Hkv, int N, int d, int block_n, void* stream) {
+    if (B < 0 || N < 0 || Hkv <= 0 || block_n <= 0) return VFA_ERR_INVALID_ARG;
+    if (d != 64 && d != 128) return VFA_ERR_UNSUPPORTED;
+    if (B == 0 || N == 0) return VFA_OK;
+    if (!K || !Krepr || !aligned16(K) || !aligned16(Krepr)) return VFA_ERR_INVALID_ARG;
+    if ((long long)B * Hkv > 65535) return VFA_ERR_UNSUPPORTED;
+    return summary_launch(K, Krepr, B, Hkv, N, d, block_n, (hipStream_t)stream);
+}
+
+int fa_baseline_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int N,
+                    int d, int block_m, int block_n, int causal, float softmax_scale, void* stream) {
+    int rc = check_common(Q, K, V, O, LSE, B, Hq, Hkv, N, d, block_m, block_n);
+    if (rc != VFA_OK) return rc;
+    if (!isfinite(softmax_scale)) return VFA_ERR_INVALID_ARG;
+    if (B == 0 || N == 0) return VFA_OK;
+    Params p{};
+    p.Q = (const uint16_t*)Q; p.K = (const uint16_t*)K; p.V = (const uint16_t*)V;
+    p.O = (uint16_t*)O; p.LSE = LSE;
+    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N; p.Tr = ceil_div(N, block_m); p.Tc = ceil_div(N, block_n);
+    p.causal = causal ? 1 : 0;
+    const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)d);
+    p.c = scale * kLog2e;
+    return launch_fwd<MODE_FA>(p, d, block_m, (hipStream_t)stream);
+}
+
+int vfa_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int N,
+                 int d, int block_m, int block_n, int causal, int n_sink, int n_local, int use_minit,
+                 float softmax_scale, void* workspace, size_t workspace_bytes, void* stream) {
+    return vfa_vsa_common(MODE_VFA, Q, K, V, O, LSE, B, Hq, Hkv, N, d, block_m, block_n, causal, n_sink, n_local,
+                          use_minit, softmax_scale, 0.f, nullptr, workspace, workspace_bytes, stream);
+}
+
+int vsa_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int N,
+                 int d, int block_m, int block_n, int causal, int n_sink, int n_local, int use_minit,
+                 float softmax_scale, float skip_threshold_nats, unsigned char* skip_mask, void* workspace,
+                 size_t workspace_bytes, void* stream) {
+    return vfa_vsa_common(MODE_VSA, Q, K, V, O, LSE, B, Hq, Hkv, N, d, block_m, block_n, causal, n_sink, n_local,
+                          use_minit, softmax_scale, skip_threshold_nats, skip_mask, workspace, workspace_bytes, stream);
+}
+
+const char* vfa_strerror(int code) {
+    switch (code) {
+        case VFA_OK: return "ok";
+        case VFA_ERR_INVALID_ARG: return "invalid argument";
+        case VFA_ERR_UNSUPPORTED: return "unsupported shape (d must be 64 or 128; blocks 64x64 or 128x64)";
+        case VFA_ERR_HIP: return "HIP launch error";
+        default: return "unknown error code";
+    }
+}
+
+}  // extern "C"

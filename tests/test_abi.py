@@ -1,0 +1,68 @@
+"""Host-side checks that need no GPU: the library loads, exports what include/vfa.h declares,
+and rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def pkg():
+    import paper_2604_12798_amd as p
+    if not os.path.exists(p.LIB_PATH):
+        from paper_2604_12798_amd import build
+        build.build_lib()
+    return p
+
+
+def test_every_declared_symbol_is_exported(pkg):
+    hdr = open(os.path.join(ROOT, "include", "vfa.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(vfa_\w+|vsa_\w+|fa_\w+)\s*\(", hdr))
+    assert names == set(pkg.EXPORTS)
+    L = pkg.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_strerror_and_workspace(pkg):
+    assert pkg.strerror(0) == "ok"
+    assert "invalid" in pkg.strerror(-1) and "unsupported" in pkg.strerror(-2) and "HIP" in pkg.strerror(-3)
+    assert pkg.workspace_bytes(2, 8, 16384, 128, 64) == 2 * 8 * 256 * 128 * 2
+    assert pkg.workspace_bytes(1, 1, 65, 64, 64) == 256          # 2 blocks * 64 * 2 bytes, rounded up
+    assert pkg.workspace_bytes(0, 1, 64, 64, 64) == 0
+
+
+def test_bad_arguments_are_rejected_before_launch(pkg):
+    L = pkg.lib()
+    p = ctypes.c_void_p(0x1000)     # never dereferenced: every call below fails validation first
+    odd = ctypes.c_void_p(0x1004)
+    none = ctypes.c_void_p(0)
+    fa = lambda *a: L.fa_baseline_fwd(*a)
+    ok_shape = (1, 4, 2, 256, 128, 128, 64, 1)
+    assert fa(none, p, p, p, none, *ok_shape, 0.0, none) == -1                 # null Q
+    assert fa(odd, p, p, p, none, *ok_shape, 0.0, none) == -1                  # misaligned
+    assert fa(p, p, p, p, none, 1, 4, 3, 256, 128, 128, 64, 1, 0.0, none) == -1  # Hq % Hkv
+    assert fa(p, p, p, p, none, 1, 4, 2, -1, 128, 128, 64, 1, 0.0, none) == -1   # negative N
+    assert fa(p, p, p, p, none, 1, 4, 2, 256, 96, 128, 64, 1, 0.0, none) == -2   # d
+    assert fa(p, p, p, p, none, 1, 4, 2, 256, 128, 128, 128, 1, 0.0, none) == -2  # block pair
+    assert fa(p, p, p, p, none, 1, 4, 2, 256, 128, 32, 64, 1, 0.0, none) == -2
+    assert fa(p, p, p, p, none, 0, 4, 2, 256, 128, 128, 64, 1, 0.0, none) == 0   # empty batch: no-op
+    assert fa(none, none, none, none, none, 1, 4, 2, 0, 128, 128, 64, 1, 0.0, none) == 0  # N = 0: no-op
+    vf = lambda *a: L.vfa_attn_fwd(*a)
+    base = (p, p, p, p, none, *ok_shape)
+    assert vf(*base, 1, 1, 1, 0.0, none, 0, none) == -1                           # workspace missing
+    assert vf(*base, 1, 1, 1, 0.0, p, 16, none) == -1                             # workspace too small
+    assert vf(*base, -1, 1, 1, 0.0, p, 1 << 20, none) == -1                       # n_sink < 0
+    assert vf(*base, 0, 0, 0, 0.0, p, 1 << 20, none) == -1                        # max would stay -inf
+    assert vf(*base, 1, 1, 1, float("nan"), p, 1 << 20, none) == -1
+    vs = lambda *a: L.vsa_attn_fwd(*a)
+    assert vs(*base, 1, 1, 1, 0.0, 0.0, none, p, 1 << 20, none) == -1             # threshold must be > 0
+    assert vs(*base, 1, 1, 1, 0.0, float("nan"), none, p, 1 << 20, none) == -1
+    assert vs(*base, 1, 1, 1, 0.0, float("inf"), none, p, 1 << 20, none) == -1
+    assert L.vfa_kblock_summary(none, p, 1, 1, 64, 128, 64, none) == -1
+    assert L.vfa_kblock_summary(p, p, 1, 1, 64, 100, 64, none) == -2
+    assert L.vfa_kblock_summary(p, p, 0, 1, 64, 128, 64, none) == 0

@@ -1,0 +1,200 @@
+"""GPU parity: the HIP path, called through the C ABI, against the float64 oracle on the same
+seeded inputs.  Bars: O max-abs <= 2e-2 and mean-abs <= 2e-3, LSE <= 1e-3, skip masks bit-exact
+(outside a 1e-3-nat guard band around the threshold), key-block summaries bit-exact."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from paper_2604_12798_amd import workloads as wl
+
+from gpu_util import MASK_GUARD_NATS, check_o_lse, gather_blocks, gpu_inputs, host_f32, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def vfa():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2604_12798_amd as pkg
+    pkg.lib()   # raises if libvfa.so is missing: no fallback
+    return pkg
+
+
+def W(base="cfg2", **kw):
+    return wl.small(wl.CONFIGS[base], **kw)
+
+
+SMALL = [
+    ("cfg1", wl.CONFIGS["cfg1"]),
+    ("cfg2_small_gqa", W(B=2, Hq=4, Hkv=2, N=1024)),
+    ("cfg2_small_noncausal", W(B=1, Hq=2, Hkv=2, N=768, causal=False)),
+    ("ragged_1000", W(B=1, Hq=2, Hkv=1, N=1000)),
+    ("ragged_77_noncausal", W(B=1, Hq=1, Hkv=1, N=77, causal=False)),
+    ("one_key", W(B=1, Hq=1, Hkv=1, N=1)),
+    ("d64_128x64", W(B=1, Hq=2, Hkv=1, N=640, d=64, F=4)),
+    ("d128_64x64", W(B=1, Hq=2, Hkv=2, N=576, block_m=64)),
+    ("sink2_local3", W(B=1, Hq=2, Hkv=1, N=1024, n_sink=2, n_local=3)),
+    ("sink0_local2_noncausal", W(B=1, Hq=1, Hkv=1, N=896, n_sink=0, n_local=2, causal=False)),
+    ("sink1_local0", W(B=1, Hq=1, Hkv=1, N=768, n_sink=1, n_local=0)),
+    ("planted_noncausal", W("cfg4", B=1, Hq=2, Hkv=2, N=2048)),
+]
+
+
+def _run_all(vfa, w, t, blocks, oracle, use_minit=True):
+    import torch
+    Q, K, V = gpu_inputs(t)
+    Qh, Kh, Vh = host_f32(t)
+    kw = dict(block_m=w.block_m, block_n=w.block_n, causal=w.causal)
+    res = {}
+    Oe, Le, Me = oracle.exact(Qh, Kh, Vh, w.block_m, w.causal, blocks)
+    O, L = vfa.fa_baseline_fwd(Q, K, V, **kw)
+    torch.cuda.synchronize()
+    res["fa"] = check_o_lse(O, L, Oe, Le, blocks, w.block_m, w.N, "fa_baseline_fwd vs exact")
+    ref = oracle.fa2(Qh, Kh, Vh, w.block_m, w.block_n, w.causal, blocks)
+    check_o_lse(O, L, ref["O"], ref["LSE"], blocks, w.block_m, w.N, "fa_baseline_fwd vs oracle FA")
+    O, L = vfa.vfa_attn_fwd(Q, K, V, n_sink=w.n_sink, n_local=w.n_local, use_minit=use_minit, **kw)
+    torch.cuda.synchronize()
+    ref = oracle.blocks(Qh, Kh, Vh, w.block_m, w.block_n, w.causal, blocks, n_sink=w.n_sink, n_local=w.n_local,
+                        use_minit=use_minit)
+    res["vfa"] = check_o_lse(O, L, ref["O"], ref["LSE"], blocks, w.block_m, w.N, "vfa_attn_fwd vs oracle VFA")
+    check_o_lse(O, L, Oe, Le, blocks, w.block_m, w.N, "vfa_attn_fwd vs exact")
+    return res
+
+
+@pytest.mark.parametrize("name,w", SMALL, ids=[n for n, _ in SMALL])
+def test_fa_and_vfa_match_oracle(vfa, oracle, name, w):
+    t = wl.generate(w)
+    print(name, _run_all(vfa, w, t, wl.all_blocks(w), oracle), flush=True)
+
+
+@pytest.mark.parametrize("name,w", [SMALL[1], SMALL[8]], ids=[SMALL[1][0], SMALL[8][0]])
+def test_vfa_without_minit(vfa, oracle, name, w):
+    t = wl.generate(w)
+    print(name, _run_all(vfa, w, t, wl.all_blocks(w), oracle, use_minit=False), flush=True)
+
+
+@pytest.mark.parametrize("name,w", SMALL[:5] + SMALL[6:9], ids=[n for n, _ in SMALL[:5] + SMALL[6:9]])
+def test_kblock_summary_bit_exact(vfa, oracle, name, w):
+    import torch
+    t = wl.generate(w)
+    K = to_gpu(t["K"])
+    R = vfa.kblock_summary(K, w.block_n)
+    torch.cuda.synchronize()
+    got = R.float().cpu().numpy().astype(np.float64)
+    want = oracle.sabsmax(wl.bf16_bits_to_f32(t["K"]), w.block_n)
+    assert got.shape == want.shape and np.array_equal(got, want)
+
+
+def test_kblock_summary_tie_takes_positive(vfa, oracle):
+    import torch
+    K = np.zeros((1, 1, 128, 64), np.float32)
+    K[0, 0, 3, :] = -2.0
+    K[0, 0, 40, :32] = 2.0          # tie in the first 32 dims: +2 wins
+    K[0, 0, 70, 5] = -0.5
+    bits = wl.f32_to_bf16_bits(K)
+    R = vfa.kblock_summary(to_gpu(bits), 64).float().cpu().numpy().astype(np.float64)
+    assert np.array_equal(R, oracle.sabsmax(K, 64))
+    assert np.all(R[0, 0, 0, :32] == 2.0) and np.all(R[0, 0, 0, 32:] == -2.0) and R[0, 0, 1, 5] == -0.5
+
+
+VSA_CASES = [
+    ("cfg1_thr3", wl.small(wl.CONFIGS["cfg1"], beta=4.0), 3.0),
+    ("small_thr4", W(B=1, Hq=4, Hkv=2, N=2048, beta=6.0, kappa=3.0), 4.0),
+    ("small_thr8", W(B=1, Hq=2, Hkv=1, N=2048, beta=6.0, kappa=3.0), 8.0),
+    ("noncausal_thr5", W(B=1, Hq=2, Hkv=2, N=1024, beta=6.0, kappa=3.0, causal=False), 5.0),
+    ("ragged_thr4", W(B=1, Hq=2, Hkv=1, N=1000, beta=6.0, kappa=3.0), 4.0),
+    ("d64_64x64_thr4", W(B=1, Hq=2, Hkv=1, N=1024, d=64, F=4, block_m=64, beta=6.0, kappa=3.0), 4.0),
+]
+
+
+@pytest.mark.parametrize("name,w,thr", VSA_CASES, ids=[c[0] for c in VSA_CASES])
+def test_vsa_mask_bit_exact_and_output(vfa, oracle, name, w, thr):
+    import torch
+    t = wl.generate(w)
+    Q, K, V = gpu_inputs(t)
+    Qh, Kh, Vh = host_f32(t)
+    blocks = wl.all_blocks(w)
+    O, L, M = vfa.vsa_attn_fwd(Q, K, V, block_m=w.block_m, block_n=w.block_n, causal=w.causal, n_sink=w.n_sink,
+                               n_local=w.n_local, skip_threshold_nats=thr)
+    torch.cuda.synchronize()
+    ref = oracle.blocks(Qh, Kh, Vh, w.block_m, w.block_n, w.causal, blocks, n_sink=w.n_sink, n_local=w.n_local,
+                        vsa=True, skip_threshold_nats=thr)
+    got = M.cpu().numpy().reshape(len(blocks), w.Tc)
+    near = np.abs(ref["margin"]) < MASK_GUARD_NATS            # NaN (not visited) compares False
+    assert near.sum() == 0, "pick another seed: a tile sits on the threshold"
+    assert np.array_equal(got, ref["mask"]), (name, int((got != ref["mask"]).sum()))
+    sparsity = (ref["mask"] == 1).sum() / max(1, (ref["mask"] != 2).sum())
+    stats = check_o_lse(O, L, ref["O"], ref["LSE"], blocks, w.block_m, w.N, "vsa_attn_fwd vs oracle VSA")
+    print(name, "sparsity %.3f" % sparsity, stats, flush=True)
+    assert sparsity > 0.02
+
+
+def test_vsa_huge_threshold_equals_vfa_bitwise(vfa):
+    import torch
+    w = W(B=1, Hq=2, Hkv=1, N=1024)
+    Q, K, V = gpu_inputs(wl.generate(w))
+    O1, L1 = vfa.vfa_attn_fwd(Q, K, V)
+    O2, L2, M = vfa.vsa_attn_fwd(Q, K, V, skip_threshold_nats=1e4)
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O2) and torch.equal(L1, L2)
+    assert int((M == 1).sum()) == 0
+
+
+def test_all_tiles_skipped_rows_are_zero(vfa, oracle):
+    """Caller-supplied summaries (use_minit=2) far above every real score make m_init huge, so
+    every tile of every row is skipped: O = 0, LSE = -inf, mask all ones."""
+    import torch
+    w = W(B=1, Hq=2, Hkv=1, N=512, causal=False, n_sink=0, n_local=0)
+    t = wl.generate(w)
+    t["Q"] = t["Q"] & np.uint16(0x7FFF)                       # |Q|: every query has positive entries only
+    Q, K, V = gpu_inputs(t)
+    Qh, Kh, Vh = host_f32(t)
+    blocks = wl.all_blocks(w)
+    planted = np.full((1, 1, w.Tc, w.d), 4.0, np.float32)   # m_init ~ 35-45 nats above the real scores
+    ws = torch.zeros(vfa.workspace_bytes(1, 1, w.N, w.d, 64), dtype=torch.uint8, device="cuda")
+    ws.view(torch.bfloat16)[: planted.size] = to_gpu(wl.f32_to_bf16_bits(planted)).flatten()
+    kw = dict(block_m=128, block_n=64, causal=False, n_sink=0, n_local=0, skip_threshold_nats=8.0)
+    O, L, M = vfa.vsa_attn_fwd(Q, K, V, use_minit=2, workspace=ws, **kw)
+    torch.cuda.synchronize()
+    ref = oracle.blocks(Qh, Kh, Vh, 128, 64, False, blocks, n_sink=0, n_local=0, vsa=True, skip_threshold_nats=8.0,
+                        krepr=planted.astype(np.float64))
+    assert np.all(ref["mask"] == 1) and np.all(ref["O"] == 0) and np.all(np.isneginf(ref["LSE"]))
+    assert int((M != 1).sum()) == 0
+    assert float(O.float().abs().max()) == 0.0 and bool(torch.isneginf(L).all())
+    # the same summaries through VFA (no skipping): m is far too high, the result is still exact attention
+    O, L = vfa.vfa_attn_fwd(Q, K, V, use_minit=2, workspace=ws, block_m=128, block_n=64, causal=False, n_sink=0, n_local=0)
+    torch.cuda.synchronize()
+    Oe, Le, _ = oracle.exact(Qh, Kh, Vh, 128, False, blocks)
+    check_o_lse(O, L, Oe, Le, blocks, 128, w.N, "vfa with an over-estimated frozen max")
+
+
+def test_deterministic(vfa):
+    import torch
+    w = W(B=1, Hq=4, Hkv=2, N=2048, beta=6.0, kappa=3.0)
+    Q, K, V = gpu_inputs(wl.generate(w))
+    a = vfa.vfa_attn_fwd(Q, K, V)
+    b = vfa.vfa_attn_fwd(Q, K, V)
+    c = vfa.vsa_attn_fwd(Q, K, V, skip_threshold_nats=4.0)
+    d = vfa.vsa_attn_fwd(Q, K, V, skip_threshold_nats=4.0)
+    e = vfa.fa_baseline_fwd(Q, K, V)
+    f = vfa.fa_baseline_fwd(Q, K, V)
+    torch.cuda.synchronize()
+    for x, y in zip(a + c + e, b + d + f):
+        assert torch.equal(x, y)
+
+
+def test_custom_scale_and_no_lse(vfa, oracle):
+    import torch
+    w = W(B=1, Hq=2, Hkv=1, N=512)
+    t = wl.generate(w)
+    Q, K, V = gpu_inputs(t)
+    Qh, Kh, Vh = host_f32(t)
+    blocks = wl.all_blocks(w)
+    O, L = vfa.vfa_attn_fwd(Q, K, V, softmax_scale=0.05)
+    O2, L2 = vfa.vfa_attn_fwd(Q, K, V, softmax_scale=0.05, want_lse=False)
+    torch.cuda.synchronize()
+    assert L2 is None and torch.equal(O, O2)
+    ref = oracle.blocks(Qh, Kh, Vh, 128, 64, True, blocks, scale=0.05)
+    check_o_lse(O, L, ref["O"], ref["LSE"], blocks, 128, 512, "custom scale")
