@@ -102,7 +102,6 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const Params p) {
     constexpr int NT = 64 * NW;
     constexpr int KK = D / 16;                 // k-steps of Q K^T
     constexpr int DB = D / 32;                 // 32-row blocks of O^T
-    constexpr int LD = (BN * T::CH) / NT;      // 16-byte chunks each thread moves per tile
 
     __shared__ __attribute__((aligned(16))) uint8_t smem[4 * T::BYTES];  // K[2], V[2]
     __shared__ int votes[2][NW];
@@ -157,30 +156,29 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const Params p) {
     for (int kk = 0; kk < KK; ++kk)
         qf[kk] = *reinterpret_cast<const bf16x8*>(Qg + (size_t)qrow_c * D + 16 * kk + 8 * hh);
 
-    // ---- tile movers: global -> registers -> LDS (swizzled)
-    u32x4 kreg[LD], vreg[LD];
-    auto load_rows = [&](const uint16_t* base, int first_row, int row_limit, u32x4* reg) {
+    // ---- tile mover: global -> LDS directly (global_load_lds_dwordx4: lane l of a wave writes
+    // 16 bytes at the wave-uniform LDS address + 16*l, so one instruction fills RPI whole rows).
+    // The swizzle is applied on the global side: the lane that owns LDS chunk position cp of row r
+    // fetches global chunk cp ^ f(r).
+    constexpr int RPI = 1024 / T::ROWB;        // rows per wave instruction
+    constexpr int NI = BN / RPI / NW;          // instructions per wave per tile
+    auto load_tile = [&](const uint16_t* base, int first_row, int row_limit, uint8_t* dst, bool is_v) {
+        const bool full = first_row + BN <= row_limit;
 #pragma unroll
-        for (int u = 0; u < LD; ++u) {
-            const int q = u * NT + tid;
-            const int r = q / T::CH, ch = q % T::CH;
-            const int gr = min(first_row + r, row_limit - 1);
-            reg[u] = *reinterpret_cast<const u32x4*>(base + (size_t)gr * D + ch * 8);
+        for (int u = 0; u < NI; ++u) {
+            const int q = u * NW + wave;
+            const int r = RPI * q + lane / T::CH;
+            const int cp = lane % T::CH;
+            const int ch = is_v ? (cp ^ ((r & (T::CH / 4 - 1)) << 2)) : (cp ^ (r & (T::CH - 1)));
+            const int gr = full ? first_row + r : min(first_row + r, row_limit - 1);
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(base + (size_t)gr * D + ch * 8),
+                (__attribute__((address_space(3))) void*)(dst + q * 1024), 16, 0, 0);
         }
     };
-    auto store_k = [&](uint8_t* dst, const u32x4* reg) {
-#pragma unroll
-        for (int u = 0; u < LD; ++u) {
-            const int q = u * NT + tid;
-            *reinterpret_cast<u32x4*>(dst + T::k_off(q / T::CH, q % T::CH)) = reg[u];
-        }
-    };
-    auto store_v = [&](uint8_t* dst, const u32x4* reg) {
-#pragma unroll
-        for (int u = 0; u < LD; ++u) {
-            const int q = u * NT + tid;
-            *reinterpret_cast<u32x4*>(dst + T::v_off(q / T::CH, q % T::CH)) = reg[u];
-        }
+    auto wait_tiles = [&]() {
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's LDS-direct loads have landed
+        __syncthreads();
     };
 
     // S^T tile: st[t][i] = score of query ql against key 32*t + 8*(i/4) + 4*hh + (i%4)
@@ -203,10 +201,9 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const Params p) {
         float mx = -INFINITY;
         const int n_sum_tiles = (j_hi + BN) / BN;
         for (int ts = 0; ts < n_sum_tiles; ++ts) {
-            load_rows(Rg, ts * BN, p.Tc, kreg);
             __syncthreads();  // previous tile's readers are done
-            store_k(Ks, kreg);
-            __syncthreads();
+            load_tile(Rg, ts * BN, p.Tc, Ks, false);
+            wait_tiles();
             f32x16 st[2];
             qk_tile(Ks, st);
 #pragma unroll
@@ -308,14 +305,12 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const Params p) {
         }
     };
 
-    // ---- main loop, double-buffered: tile k+1 travels global -> registers while tile k computes
+    // ---- main loop, double-buffered: tile k+1 streams into the other LDS buffer while tile k computes
     {
         const int j0 = vis.tile(0);
-        load_rows(Kg, j0 * BN, N, kreg);
-        load_rows(Vg, j0 * BN, N, vreg);
-        store_k(Ks, kreg);
-        store_v(Vs, vreg);
-        __syncthreads();
+        load_tile(Kg, j0 * BN, N, Ks, false);
+        load_tile(Vg, j0 * BN, N, Vs, true);
+        wait_tiles();
     }
     for (int k = 0; k < vis.total; ++k) {
         const int j = vis.tile(k);
@@ -323,8 +318,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const Params p) {
         const bool more = k + 1 < vis.total;
         if (more) {
             const int jn = vis.tile(k + 1);
-            load_rows(Kg, jn * BN, N, kreg);
-            load_rows(Vg, jn * BN, N, vreg);
+            load_tile(Kg, jn * BN, N, Ks + (buf ^ 1) * T::BYTES, false);
+            load_tile(Vg, jn * BN, N, Vs + (buf ^ 1) * T::BYTES, true);
         }
         const bool special = k < vis.n_special;
         const bool masked = (p.causal && j * BN + BN - 1 > row0) || (j + 1) * BN > N;
@@ -364,11 +359,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const Params p) {
                 else softmax_pv(st, vt, j, false, false);
             }
         }
-        if (more) {
-            store_k(Ks + (buf ^ 1) * T::BYTES, kreg);
-            store_v(Vs + (buf ^ 1) * T::BYTES, vreg);
-        }
-        __syncthreads();
+        wait_tiles();
     }
 
     // ---- epilogue: O = O^T / l, LSE = (m2 + log2 l) ln 2
