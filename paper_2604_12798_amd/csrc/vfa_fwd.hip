@@ -61,6 +61,15 @@ struct Tile {
     static constexpr int BYTES = BN * ROWB;
     __device__ static int k_off(int row, int chunk) { return row * ROWB + ((chunk ^ (row & (CH - 1))) << 4); }
     __device__ static int v_off(int row, int chunk) { return row * ROWB + ((chunk ^ ((row & (CH / 4 - 1)) << 2)) << 4); }
+    // Per-lane bases from which every fragment address of a tile follows by XOR with a constant
+    // (the swizzles are XORs, so the varying index bits commute with them):
+    //   K fragment (t, kk) of lane (ql, hh):  (k_base(ql, hh) ^ (kk << 5)) + t * 32 * ROWB
+    //   V fragment (c, u, db) of a lane:      (v_base(lane, hh) ^ (db << 6)) + (16 c + 8 u) * ROWB
+    __device__ static int k_base(int ql, int hh) { return ql * ROWB + ((hh ^ (ql & (CH - 1))) << 4); }
+    __device__ static int v_base(int lane, int hh) {
+        const int s = lane & 15, dsel = (lane >> 4) & 1, row = 4 * hh + (s >> 2);
+        return row * ROWB + (((2 * dsel + ((s & 3) >> 1)) ^ ((row & (CH / 4 - 1)) << 2)) << 4) + ((s & 1) << 3);
+    }
 };
 
 __device__ inline float xhalf_max(float x) {
@@ -95,13 +104,199 @@ struct Visit {
     }
 };
 
+template <int MODE>
+__device__ inline Visit make_visit(const Params& p, int a_lo, int a_hi, int j_hi) {
+    Visit vis;
+    vis.n1 = 0; vis.s2 = 0; vis.n2 = 0;
+    vis.total = j_hi + 1;
+    if (MODE == MODE_FA) {
+        vis.n_special = vis.total;
+    } else {
+        vis.n1 = min(p.n_sink, j_hi + 1);
+        if (p.n_local > 0) {
+            const int lo = max(max(0, a_lo - (p.n_local - 1)), vis.n1), hi = min(a_hi, j_hi);
+            if (hi >= lo) { vis.s2 = lo; vis.n2 = hi - lo + 1; }
+        }
+        vis.n_special = vis.n1 + vis.n2;
+    }
+    return vis;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Tile mover: global -> LDS directly (global_load_lds_dwordx4: lane l of a wave writes 16 bytes
+// at the wave-uniform LDS address + 16*l, so one instruction fills RPI whole rows).  The swizzle
+// is applied on the global side: the lane that owns LDS chunk position cp of row r fetches
+// global chunk cp ^ f(r).  NWAVES waves share the tile's instructions round-robin.
+template <int D, int NWAVES>
+__device__ __forceinline__ void load_tile(const uint16_t* base, int first_row, int row_limit, uint8_t* dst,
+                                          bool is_v, int wave, int lane) {
+    using T = Tile<D>;
+    constexpr int RPI = 1024 / T::ROWB;  // rows per wave instruction
+    constexpr int NI = BN / RPI / NWAVES;  // instructions per wave per tile
+    static_assert(NI >= 1, "too many waves for this tile");
+    const bool full = first_row + BN <= row_limit;
+#pragma unroll
+    for (int u = 0; u < NI; ++u) {
+        const int q = u * NWAVES + wave;
+        const int r = RPI * q + lane / T::CH;
+        const int cp = lane % T::CH;
+        const int ch = is_v ? (cp ^ ((r & (T::CH / 4 - 1)) << 2)) : (cp ^ (r & (T::CH - 1)));
+        const int gr = full ? first_row + r : min(first_row + r, row_limit - 1);
+        // Written as inline asm on purpose: the compiler's wait-count pass treats every LDS read as
+        // dependent on every outstanding LDS-direct load and would drain them all (vmcnt(0)) before the
+        // first ds_read of a phase, which defeats the prefetch.  The callers wait explicitly instead.
+        const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
+            (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)(dst + q * 1024));
+        const uint16_t* src = base + (size_t)gr * D + ch * 8;
+        uint32_t m0_save;  // M0 carries the LDS base of the load; put back what the compiler had there
+        asm volatile(
+            "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+            : "=&s"(m0_save)
+            : "s"(lds_addr), "v"(src)
+            : "memory");
+    }
+}
+
+// S^T tile: st[t][i] = raw score of query ql against key 32*t + 8*(i/4) + 4*hh + (i%4)
+template <int D>
+__device__ __forceinline__ void qk_tile(const uint8_t* kt, const bf16x8* qf, f32x16* st, int ql, int hh) {
+    using T = Tile<D>;
+    st[0] = f32x16{0};
+    st[1] = f32x16{0};
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kt + T::k_off(32 * t + ql, 2 * kk + hh));
+            st[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], st[t], 0, 0, 0);
+        }
+}
+
+// in-lane max of a score tile, entries with key index > limit excluded when MASKED
+template <bool MASKED>
+__device__ __forceinline__ float tile_rowmax(const f32x16* st, int key0, int limit, int hh) {
+    float mx = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int key = key0 + 32 * t + 8 * (r >> 2) + 4 * hh + (r & 3);
+            mx = fmaxf(mx, (!MASKED || key <= limit) ? st[t][r] : -INFINITY);
+        }
+    return mx;
+}
+
+// Softmax step of one tile for this lane's query: st (raw scores) -> pk (exp, bf16 pairs),
+// lsum += row sum.  SPECIAL: exact online-softmax update of m2 with rescale of lsum and ot;
+// otherwise m2 is frozen: no row max, no rescale (Alg. 1 / Table 1).
+template <bool SPECIAL, bool MASKED, int DB>
+__device__ __forceinline__ void softmax_tile(f32x16* st, uint32_t* pk, f32x16* ot, float& m2, float& lsum, float c,
+                                             int key0, int limit, int hh) {
+    if (MASKED) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = key0 + 32 * t + 8 * (r >> 2) + 4 * hh + (r & 3);
+                st[t][r] = key <= limit ? st[t][r] : -INFINITY;
+            }
+    }
+    float msub = m2;
+    if (SPECIAL) {
+        const float mx = tile_rowmax<false>(st, 0, 0, hh);
+        const float m_new = fmaxf(m2, xhalf_max(mx) * c);
+        msub = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m2 - msub);
+        lsum *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) ot[db] *= alpha;
+        m2 = m_new;
+    }
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[t][r], c, -msub));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[t][r + 1], c, -msub));
+            lsum += p0;
+            lsum += p1;
+            pk[8 * t + (r >> 1)] = pack_bf16(p0, p1);
+        }
+}
+
+__device__ __forceinline__ void softmax_dispatch4(bool special, bool masked, f32x16* st, uint32_t* pk, f32x16* ot,
+                                                  float& m2, float& lsum, float c, int key0, int limit, int hh) {
+    if (special) {
+        if (masked) softmax_tile<true, true, 4>(st, pk, ot, m2, lsum, c, key0, limit, hh);
+        else softmax_tile<true, false, 4>(st, pk, ot, m2, lsum, c, key0, limit, hh);
+    } else {
+        if (masked) softmax_tile<false, true, 4>(st, pk, ot, m2, lsum, c, key0, limit, hh);
+        else softmax_tile<false, false, 4>(st, pk, ot, m2, lsum, c, key0, limit, hh);
+    }
+}
+
+// O^T += V^T P^T for one tile.  P^T fragment of key chunk c (16 keys) = registers 8*(c&1)..+7 of
+// st[c >> 1] in order, i.e. pk[4c..4c+3]; the matching V^T fragment: lane gets
+// V[16c + 8u + 4hh + e][32db + (lane & 31)], e = 0..3, u = 0, 1, via two transposing reads.
+template <int D>
+__device__ __forceinline__ void pv_tile(const uint8_t* vt, const uint32_t* pk, f32x16* ot, int lane, int hh) {
+    using T = Tile<D>;
+    const int s = lane & 15, dsel = (lane >> 4) & 1;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const u32x4 pw = {pk[4 * c], pk[4 * c + 1], pk[4 * c + 2], pk[4 * c + 3]};
+        const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db) {
+            const int chunk = 4 * db + 2 * dsel + ((s & 3) >> 1);
+            const int key0 = 16 * c + 4 * hh + (s >> 2);
+            const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) s16x4*)(vt + T::v_off(key0, chunk) + ((s & 1) << 3)));
+            const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) s16x4*)(vt + T::v_off(key0 + 8, chunk) + ((s & 1) << 3)));
+            const u32x2 a0 = __builtin_bit_cast(u32x2, v0), a1 = __builtin_bit_cast(u32x2, v1);
+            const u32x4 aw = {a0[0], a0[1], a1[0], a1[1]};
+            ot[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aw), pf, ot[db], 0, 0, 0);
+        }
+    }
+}
+
+// O = O^T / l (bf16, round to nearest even), LSE = (m2 + log2 l) ln 2
+template <int D>
+__device__ __forceinline__ void store_output(const Params& p, const f32x16* ot, float m2, float lsum, int b, int h,
+                                             int qrow, int hh) {
+    const float l = xhalf_sum(lsum);
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    if (qrow < p.N) {
+        uint16_t* Og = p.O + ((size_t)(b * p.Hq + h) * p.N + qrow) * D;
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const u32x2 w = {pack_bf16(ot[db][4 * q4] * inv, ot[db][4 * q4 + 1] * inv),
+                                 pack_bf16(ot[db][4 * q4 + 2] * inv, ot[db][4 * q4 + 3] * inv)};
+                *reinterpret_cast<u32x2*>(Og + 32 * db + 8 * q4 + 4 * hh) = w;
+            }
+        if (p.LSE && hh == 0)
+            p.LSE[(size_t)(b * p.Hq + h) * p.N + qrow] = l > 0.f ? (m2 + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
+    }
+}
+
+__device__ __forceinline__ void wait_vm0_and_sync() {
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's LDS-direct loads have landed
+    __syncthreads();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Generic kernel: any supported (d, block_m); NW waves, one query block per workgroup, two
+// workgroups per CU.  Tile k+1 streams into the other LDS buffer while tile k computes.
 template <int D, int NW, int MODE>
 __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const Params p) {
     using T = Tile<D>;
     constexpr int BM = 32 * NW;
     constexpr int NT = 64 * NW;
-    constexpr int KK = D / 16;                 // k-steps of Q K^T
-    constexpr int DB = D / 32;                 // 32-row blocks of O^T
+    constexpr int KK = D / 16;  // k-steps of Q K^T
+    constexpr int DB = D / 32;  // 32-row blocks of O^T
 
     __shared__ __attribute__((aligned(16))) uint8_t smem[4 * T::BYTES];  // K[2], V[2]
     __shared__ int votes[2][NW];
@@ -110,7 +305,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const Params p) {
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it in an SGPR
     const int ql = lane & 31;  // query column inside the wave
     const int hh = lane >> 5;  // which half of the k / row split this lane holds
 
@@ -151,48 +346,11 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const Params p) {
     // ---- Q fragments: B operand of S^T = K Q^T; lane holds Q[row0 + 32*wave + ql][16*kk + 8*hh .. +7]
     const int qrow = row0 + 32 * wave + ql;
     const int qrow_c = min(qrow, N - 1);
+    const int limit = p.causal ? qrow_c : N - 1;  // last visible key of this lane's query
     bf16x8 qf[KK];
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk)
         qf[kk] = *reinterpret_cast<const bf16x8*>(Qg + (size_t)qrow_c * D + 16 * kk + 8 * hh);
-
-    // ---- tile mover: global -> LDS directly (global_load_lds_dwordx4: lane l of a wave writes
-    // 16 bytes at the wave-uniform LDS address + 16*l, so one instruction fills RPI whole rows).
-    // The swizzle is applied on the global side: the lane that owns LDS chunk position cp of row r
-    // fetches global chunk cp ^ f(r).
-    constexpr int RPI = 1024 / T::ROWB;        // rows per wave instruction
-    constexpr int NI = BN / RPI / NW;          // instructions per wave per tile
-    auto load_tile = [&](const uint16_t* base, int first_row, int row_limit, uint8_t* dst, bool is_v) {
-        const bool full = first_row + BN <= row_limit;
-#pragma unroll
-        for (int u = 0; u < NI; ++u) {
-            const int q = u * NW + wave;
-            const int r = RPI * q + lane / T::CH;
-            const int cp = lane % T::CH;
-            const int ch = is_v ? (cp ^ ((r & (T::CH / 4 - 1)) << 2)) : (cp ^ (r & (T::CH - 1)));
-            const int gr = full ? first_row + r : min(first_row + r, row_limit - 1);
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(base + (size_t)gr * D + ch * 8),
-                (__attribute__((address_space(3))) void*)(dst + q * 1024), 16, 0, 0);
-        }
-    };
-    auto wait_tiles = [&]() {
-        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's LDS-direct loads have landed
-        __syncthreads();
-    };
-
-    // S^T tile: st[t][i] = score of query ql against key 32*t + 8*(i/4) + 4*hh + (i%4)
-    auto qk_tile = [&](const uint8_t* kt, f32x16* st) {
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            st[t] = f32x16{0};
-#pragma unroll
-            for (int kk = 0; kk < KK; ++kk) {
-                const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kt + T::k_off(32 * t + ql, 2 * kk + hh));
-                st[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], st[t], 0, 0, 0);
-            }
-        }
-    };
 
     // ---- m-initialisation: m2 = c * max_j Q_i . Krepr_j over visible key blocks (raw scores here)
     float m2 = -INFINITY;
@@ -202,38 +360,17 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const Params p) {
         const int n_sum_tiles = (j_hi + BN) / BN;
         for (int ts = 0; ts < n_sum_tiles; ++ts) {
             __syncthreads();  // previous tile's readers are done
-            load_tile(Rg, ts * BN, p.Tc, Ks, false);
-            wait_tiles();
+            load_tile<D, NW>(Rg, ts * BN, p.Tc, Ks, false, wave, lane);
+            wait_vm0_and_sync();
             f32x16 st[2];
-            qk_tile(Ks, st);
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int j = ts * BN + 32 * t + 8 * (r >> 2) + 4 * hh + (r & 3);
-                    mx = fmaxf(mx, j <= j_hi ? st[t][r] : -INFINITY);
-                }
+            qk_tile<D>(Ks, qf, st, ql, hh);
+            mx = fmaxf(mx, tile_rowmax<true>(st, ts * BN, j_hi, hh));
         }
         m2 = xhalf_max(mx) * p.c;
         __syncthreads();
     }
 
-    // ---- visit order
-    Visit vis;
-    if (MODE == MODE_FA) {
-        vis.n1 = 0; vis.s2 = 0; vis.n2 = 0;
-        vis.total = j_hi + 1;
-        vis.n_special = vis.total;
-    } else {
-        vis.n1 = min(p.n_sink, j_hi + 1);
-        vis.n2 = 0; vis.s2 = 0;
-        if (p.n_local > 0) {
-            const int lo = max(max(0, a_lo - (p.n_local - 1)), vis.n1), hi = min(a_hi, j_hi);
-            if (hi >= lo) { vis.s2 = lo; vis.n2 = hi - lo + 1; }
-        }
-        vis.total = j_hi + 1;
-        vis.n_special = vis.n1 + vis.n2;
-    }
+    const Visit vis = make_visit<MODE>(p, a_lo, a_hi, j_hi);
 
     if (MODE == MODE_VSA && p.mask) {  // tiles this query block never visits
         uint8_t* mrow = p.mask + ((size_t)(b * p.Hq + h) * p.Tr + i) * p.Tc;
@@ -245,98 +382,28 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const Params p) {
     for (int db = 0; db < DB; ++db) ot[db] = f32x16{0};
     float lsum = 0.f;  // this lane's share of l (its 32 of the 64 keys of every tile)
 
-    // one tile: softmax on st, then O^T += V^T P^T
-    auto softmax_pv = [&](f32x16* st, const uint8_t* vt, int j, bool special, bool masked) {
-        if (masked) {
-            const int limit = p.causal ? min(qrow, N - 1) : N - 1;  // last visible key of this query
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int key = j * BN + 32 * t + 8 * (r >> 2) + 4 * hh + (r & 3);
-                    st[t][r] = key <= limit ? st[t][r] : -INFINITY;
-                }
-        }
-        float msub = m2;
-        if (special) {
-            float mx = -INFINITY;
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, st[t][r]);
-            const float m_new = fmaxf(m2, xhalf_max(mx) * p.c);
-            msub = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f(m2 - msub);
-            lsum *= alpha;
-#pragma unroll
-            for (int db = 0; db < DB; ++db) ot[db] *= alpha;
-            m2 = m_new;
-        }
-        uint32_t pk[16];
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int r = 0; r < 16; r += 2) {
-                const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[t][r], p.c, -msub));
-                const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[t][r + 1], p.c, -msub));
-                lsum += p0;
-                lsum += p1;
-                pk[8 * t + (r >> 1)] = pack_bf16(p0, p1);
-            }
-        // P^T fragment of key chunk c (16 keys): registers 8*(c&1) .. +7 of st[c >> 1], in order
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const u32x4 pw = {pk[4 * c], pk[4 * c + 1], pk[4 * c + 2], pk[4 * c + 3]};
-            const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                // V^T fragment: lane gets V[16c + 8u + 4hh + e][32db + (lane & 31)], e = 0..3, u = 0, 1
-                const int s = lane & 15, dsel = (lane >> 4) & 1;
-                const int chunk = 4 * db + 2 * dsel + ((s & 3) >> 1);
-                const int key0 = 16 * c + 4 * hh + (s >> 2);
-                const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) s16x4*)(vt + T::v_off(key0, chunk) + ((s & 1) << 3)));
-                const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) s16x4*)(vt + T::v_off(key0 + 8, chunk) + ((s & 1) << 3)));
-                const u32x2 a0 = __builtin_bit_cast(u32x2, v0), a1 = __builtin_bit_cast(u32x2, v1);
-                const u32x4 aw = {a0[0], a0[1], a1[0], a1[1]};
-                ot[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aw), pf, ot[db], 0, 0, 0);
-            }
-        }
-    };
-
-    // ---- main loop, double-buffered: tile k+1 streams into the other LDS buffer while tile k computes
     {
         const int j0 = vis.tile(0);
-        load_tile(Kg, j0 * BN, N, Ks, false);
-        load_tile(Vg, j0 * BN, N, Vs, true);
-        wait_tiles();
+        load_tile<D, NW>(Kg, j0 * BN, N, Ks, false, wave, lane);
+        load_tile<D, NW>(Vg, j0 * BN, N, Vs, true, wave, lane);
+        wait_vm0_and_sync();
     }
     for (int k = 0; k < vis.total; ++k) {
         const int j = vis.tile(k);
         const int buf = k & 1;
-        const bool more = k + 1 < vis.total;
-        if (more) {
+        if (k + 1 < vis.total) {
             const int jn = vis.tile(k + 1);
-            load_tile(Kg, jn * BN, N, Ks + (buf ^ 1) * T::BYTES, false);
-            load_tile(Vg, jn * BN, N, Vs + (buf ^ 1) * T::BYTES, true);
+            load_tile<D, NW>(Kg, jn * BN, N, Ks + (buf ^ 1) * T::BYTES, false, wave, lane);
+            load_tile<D, NW>(Vg, jn * BN, N, Vs + (buf ^ 1) * T::BYTES, true, wave, lane);
         }
         const bool special = k < vis.n_special;
         const bool masked = (p.causal && j * BN + BN - 1 > row0) || (j + 1) * BN > N;
         f32x16 st[2];
-        qk_tile(Ks + buf * T::BYTES, st);
+        qk_tile<D>(Ks + buf * T::BYTES, qf, st, ql, hh);
         bool keep = true;
         if (MODE == MODE_VSA) {
             // block vote: skip iff every row of the query block has m~ < m - threshold
-            const int limit = p.causal ? min(qrow, N - 1) : N - 1;
-            float mx = -INFINITY;
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int key = j * BN + 32 * t + 8 * (r >> 2) + 4 * hh + (r & 3);
-                    mx = fmaxf(mx, (!masked || key <= limit) ? st[t][r] : -INFINITY);
-                }
+            const float mx = masked ? tile_rowmax<true>(st, j * BN, limit, hh) : tile_rowmax<false>(st, 0, 0, hh);
             const float mt2 = xhalf_max(mx) * p.c;
             const bool row_keeps = (qrow < N) && (mt2 != -INFINITY) && !(mt2 < m2 - p.thr2);
             const bool wave_keeps = __builtin_amdgcn_ballot_w64(row_keeps) != 0;
@@ -346,38 +413,272 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const Params p) {
 #pragma unroll
             for (int w = 0; w < NW; ++w) any |= votes[buf][w];
             keep = any != 0;
-            if (p.mask && tid == 0)
-                p.mask[((size_t)(b * p.Hq + h) * p.Tr + i) * p.Tc + j] = keep ? 0 : 1;
+            if (p.mask && tid == 0) p.mask[((size_t)(b * p.Hq + h) * p.Tr + i) * p.Tc + j] = keep ? 0 : 1;
         }
         if (keep) {
-            const uint8_t* vt = Vs + buf * T::BYTES;
+            uint32_t pk[16];
             if (special) {
-                if (masked) softmax_pv(st, vt, j, true, true);
-                else softmax_pv(st, vt, j, true, false);
+                if (masked) softmax_tile<true, true, DB>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh);
+                else softmax_tile<true, false, DB>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh);
             } else {
-                if (masked) softmax_pv(st, vt, j, false, true);
-                else softmax_pv(st, vt, j, false, false);
+                if (masked) softmax_tile<false, true, DB>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh);
+                else softmax_tile<false, false, DB>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh);
             }
+            pv_tile<D>(Vs + buf * T::BYTES, pk, ot, lane, hh);
         }
-        wait_tiles();
+        wait_vm0_and_sync();
+    }
+    store_output<D>(p, ot, m2, lsum, b, h, qrow, hh);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Ping-pong kernel for d = 128, block_m = 128, an even number of query heads per KV head.
+// One workgroup = 8 waves = two groups of 4; group G handles query head 2*hp + G of the same KV
+// head at the same query block, so both groups walk the same K/V tile sequence and every tile is
+// fetched once for 256 query rows.  The two waves that share a SIMD belong to different groups
+// and run one phase apart: while one issues MFMAs (P.V of the previous tile, then Q.K^T of the
+// current one) the other runs its softmax on the vector ALU.  Workgroup barriers mark the phase
+// boundaries and keep the stagger.  K/V tiles sit in a 4-deep LDS ring filled two tiles ahead.
+constexpr int PP_STAGES = 4;
+constexpr int PP_LDS_BYTES = 2 * PP_STAGES * Tile<128>::BYTES;
+
+template <int MODE>
+__global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
+    constexpr int D = 128;
+    using T = Tile<D>;
+    constexpr int BM = 128, KK = D / 16, DB = D / 32, NWV = 8;
+    extern __shared__ __attribute__((aligned(16))) uint8_t pp_smem[];
+    __shared__ int votes[2][2][4];
+    uint8_t* const Ks = pp_smem;
+    uint8_t* const Vs = pp_smem + PP_STAGES * T::BYTES;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it in an SGPR
+    const int grp = wave >> 2;  // which query head of the pair
+    const int w4 = wave & 3;    // 32-row slice of the query block
+    const int ql = lane & 31;
+    const int hh = lane >> 5;
+
+    const int g = p.Hq / p.Hkv, gp = g >> 1;
+    const int G = p.B * p.Hkv;
+    int b, hkv, hp, i;
+    {
+        const int id = blockIdx.x;
+        if ((G & 7) == 0) {
+            const int x = id & 7, y = id >> 3;
+            const int per = p.Tr * gp;
+            const int kvl = y / per, rem = y - kvl * per;
+            i = p.Tr - 1 - rem / gp;
+            hp = rem % gp;
+            const int kv = kvl * 8 + x;
+            b = kv / p.Hkv;
+            hkv = kv - b * p.Hkv;
+        } else {
+            const int per = G * gp;
+            i = p.Tr - 1 - id / per;
+            const int rem = id % per;
+            hp = rem % gp;
+            const int kv = rem / gp;
+            b = kv / p.Hkv;
+            hkv = kv - b * p.Hkv;
+        }
+    }
+    const int h = hkv * g + 2 * hp + grp;
+    const int N = p.N;
+    const int row0 = i * BM;
+    const int last_row = min(N, row0 + BM) - 1;
+    const int a_lo = row0 / BN, a_hi = last_row / BN;
+    const int j_hi = p.causal ? a_hi : p.Tc - 1;
+
+    const uint16_t* Qg = p.Q + ((size_t)(b * p.Hq + h) * N) * D;
+    const uint16_t* Kg = p.K + ((size_t)(b * p.Hkv + hkv) * N) * D;
+    const uint16_t* Vg = p.V + ((size_t)(b * p.Hkv + hkv) * N) * D;
+
+    const int qrow = row0 + 32 * w4 + ql;
+    const int qrow_c = min(qrow, N - 1);
+    const int limit = p.causal ? qrow_c : N - 1;
+    bf16x8 qf[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk)
+        qf[kk] = *reinterpret_cast<const bf16x8*>(Qg + (size_t)qrow_c * D + 16 * kk + 8 * hh);
+
+    float m2 = -INFINITY;
+    if (MODE != MODE_FA && p.use_minit) {
+        const uint16_t* Rg = p.Krepr + ((size_t)(b * p.Hkv + hkv) * p.Tc) * D;
+        float mx = -INFINITY;
+        const int n_sum_tiles = (j_hi + BN) / BN;
+        for (int ts = 0; ts < n_sum_tiles; ++ts) {
+            __syncthreads();
+            load_tile<D, NWV>(Rg, ts * BN, p.Tc, Ks, false, wave, lane);
+            wait_vm0_and_sync();
+            f32x16 st[2];
+            qk_tile<D>(Ks, qf, st, ql, hh);
+            mx = fmaxf(mx, tile_rowmax<true>(st, ts * BN, j_hi, hh));
+        }
+        m2 = xhalf_max(mx) * p.c;
+        __syncthreads();
     }
 
-    // ---- epilogue: O = O^T / l, LSE = (m2 + log2 l) ln 2
-    const float l = xhalf_sum(lsum);
-    const float inv = l > 0.f ? 1.f / l : 0.f;
-    if (qrow < N) {
-        uint16_t* Og = p.O + ((size_t)(b * p.Hq + h) * N + qrow) * D;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const u32x2 w = {pack_bf16(ot[db][4 * q4] * inv, ot[db][4 * q4 + 1] * inv),
-                                 pack_bf16(ot[db][4 * q4 + 2] * inv, ot[db][4 * q4 + 3] * inv)};
-                *reinterpret_cast<u32x2*>(Og + 32 * db + 8 * q4 + 4 * hh) = w;
-            }
-        if (p.LSE && hh == 0)
-            p.LSE[(size_t)(b * p.Hq + h) * N + qrow] = l > 0.f ? (m2 + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
+    const Visit vis = make_visit<MODE>(p, a_lo, a_hi, j_hi);
+    const int nv = vis.total;
+    uint8_t* mrow = nullptr;
+    if (MODE == MODE_VSA && p.mask) {
+        mrow = p.mask + ((size_t)(b * p.Hq + h) * p.Tr + i) * p.Tc;
+        for (int j = j_hi + 1 + (tid & 255); j < p.Tc; j += 256) mrow[j] = 2;
     }
+
+    f32x16 ot[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) ot[db] = f32x16{0};
+    float lsum = 0.f;
+    f32x16 st[2];
+    uint32_t pk[16];
+    bool pv_pending = false;  // pk holds a tile whose P.V has not been accumulated yet
+
+    auto issue = [&](int k) {  // tile of visit k -> ring slot k & 3
+        const int j = vis.tile(k);
+        load_tile<D, NWV>(Kg, j * BN, N, Ks + (k & 3) * T::BYTES, false, wave, lane);
+        load_tile<D, NWV>(Vg, j * BN, N, Vs + (k & 3) * T::BYTES, true, wave, lane);
+    };
+    auto tile_masked = [&](int j) { return (p.causal && j * BN + BN - 1 > row0) || (j + 1) * BN > N; };
+
+    // ---- fragment loaders.  ld_v: the 4 V^T fragments (db = 0..3) of key chunk c; ld_k: the 4 K
+    // fragments (kk, t) = (2*kk2, 0), (2*kk2, 1), (2*kk2+1, 0), (2*kk2+1, 1).
+    const int kbase = T::k_base(ql, hh), vbase = T::v_base(lane, hh);
+    auto ld_v = [&](bf16x8* f, const uint8_t* vt, int c) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            const uint8_t* a = vt + (vbase ^ (db << 6)) + 16 * c * T::ROWB;
+            const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(a));
+            const s16x4 v1 =
+                __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(a + 8 * T::ROWB));
+            const u32x2 a0 = __builtin_bit_cast(u32x2, v0), a1 = __builtin_bit_cast(u32x2, v1);
+            const u32x4 aw = {a0[0], a0[1], a1[0], a1[1]};
+            f[db] = __builtin_bit_cast(bf16x8, aw);
+        }
+    };
+    auto ld_k = [&](bf16x8* f, const uint8_t* kt, int kk2) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int kk = 2 * kk2 + (e >> 1), t = e & 1;
+            f[e] = *reinterpret_cast<const bf16x8*>(kt + (kbase ^ (kk << 5)) + t * 32 * T::ROWB);
+        }
+    };
+    auto pv4 = [&](const bf16x8* f, int c) {
+        const u32x4 pw = {pk[4 * c], pk[4 * c + 1], pk[4 * c + 2], pk[4 * c + 3]};
+        const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) ot[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[db], pf, ot[db], 0, 0, 0);
+    };
+    auto qk4 = [&](const bf16x8* f, int kk2) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int kk = 2 * kk2 + (e >> 1), t = e & 1;
+            st[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[e], qf[kk], st[t], 0, 0, 0);
+        }
+    };
+    bf16x8 fa[4], fb[4];  // fragment double buffer of the matrix phase
+
+    auto issue_ahead = [&](int k) {  // at the start of matrix phase k: fetch visit k+2, make visit k+1 resident
+        if (k + 2 < nv) {
+            issue(k + 2);
+            __builtin_amdgcn_s_waitcnt(0x0F74);  // vmcnt(4): everything but the 4 loads just issued has landed
+        } else {
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+        }
+    };
+    auto vote = [&](int k) {  // VSA: this wave's say on "skip the tile of visit k"
+        const int j = vis.tile(k);
+        const float mx = tile_masked(j) ? tile_rowmax<true>(st, j * BN, limit, hh) : tile_rowmax<false>(st, 0, 0, hh);
+        const float mt2 = xhalf_max(mx) * p.c;
+        const bool row_keeps = (qrow < N) && (mt2 != -INFINITY) && !(mt2 < m2 - p.thr2);
+        const bool wave_keeps = __builtin_amdgcn_ballot_w64(row_keeps) != 0;
+        if (lane == 0) votes[k & 1][grp][w4] = wave_keeps ? 1 : 0;
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the vote is in LDS before the phase barrier
+    };
+
+    // Matrix phase of visit k in the steady state: P.V of visit k-1 (its chunk-0 fragments are already
+    // in fa, fetched at the end of the vector phase), then Q.K^T of visit k.  Fragments for the next
+    // four MFMAs are read from LDS while the current four issue.
+    auto matrix_phase_full = [&](int k) {
+        const uint8_t* vt = Vs + ((k - 1) & 3) * T::BYTES;
+        const uint8_t* kt = Ks + (k & 3) * T::BYTES;
+        issue_ahead(k);
+        __builtin_amdgcn_s_setprio(1);
+        st[0] = f32x16{0};
+        st[1] = f32x16{0};
+        ld_v(fb, vt, 1); pv4(fa, 0);
+        ld_v(fa, vt, 2); pv4(fb, 1);
+        ld_v(fb, vt, 3); pv4(fa, 2);
+        ld_k(fa, kt, 0); pv4(fb, 3);
+        ld_k(fb, kt, 1); qk4(fa, 0);
+        ld_k(fa, kt, 2); qk4(fb, 1);
+        ld_k(fb, kt, 3); qk4(fa, 2);
+        qk4(fb, 3);
+#pragma unroll
+        for (int gq = 0; gq < 3; ++gq)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // 2 LDS reads
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // 1 MFMA
+            }
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            }
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+        if (MODE == MODE_VSA) vote(k);
+        __builtin_amdgcn_s_setprio(0);
+    };
+    // Matrix phase without a pending P.V (first visit, or the previous tile was skipped): Q.K^T only.
+    auto matrix_phase_qk = [&](int k) {
+        issue_ahead(k);
+        __builtin_amdgcn_s_setprio(1);
+        qk_tile<D>(Ks + (k & 3) * T::BYTES, qf, st, ql, hh);
+        if (MODE == MODE_VSA) vote(k);
+        __builtin_amdgcn_s_setprio(0);
+    };
+    // vector phase of visit k: softmax (or the skip decision) on the scores the matrix phase left in st
+    auto vector_phase = [&](int k) {
+        const int j = vis.tile(k);
+        bool keep = true;
+        if (MODE == MODE_VSA) {
+            keep = (votes[k & 1][grp][0] | votes[k & 1][grp][1] | votes[k & 1][grp][2] | votes[k & 1][grp][3]) != 0;
+            if (mrow && (tid & 255) == 0) mrow[j] = keep ? 0 : 1;
+        }
+        pv_pending = keep;
+        if (keep) {
+            softmax_dispatch4(k < vis.n_special, tile_masked(j), st, pk, ot, m2, lsum, p.c, j * BN, limit, hh);
+            ld_v(fa, Vs + (k & 3) * T::BYTES, 0);  // first fragments of the coming P.V, in flight over the barrier
+        }
+    };
+
+    issue(0);
+    if (nv > 1) issue(1);
+    wait_vm0_and_sync();
+    if (grp == 1) __builtin_amdgcn_s_barrier();  // group 1 runs one phase behind group 0
+    for (int k = 0; k < nv; ++k) {
+        if (pv_pending) matrix_phase_full(k);
+        else matrix_phase_qk(k);
+        __builtin_amdgcn_s_barrier();
+        vector_phase(k);
+        __builtin_amdgcn_s_barrier();
+    }
+    if (pv_pending) {  // drain the last P.V
+        const uint8_t* vt = Vs + ((nv - 1) & 3) * T::BYTES;
+        pv4(fa, 0);
+#pragma unroll
+        for (int c = 1; c < 4; ++c) {
+            ld_v(fb, vt, c);
+            pv4(fb, c);
+        }
+    }
+    if (grp == 0) __builtin_amdgcn_s_barrier();
+    store_output<D>(p, ot, m2, lsum, b, h, qrow, hh);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -443,8 +744,21 @@ int check_common(const void* Q, const void* K, const void* V, void* O, const flo
 
 template <int MODE>
 int launch_fwd(const Params& p, int d, int block_m, hipStream_t s) {
-    const dim3 grid((unsigned)(p.B * p.Hq * p.Tr));
     (void)hipGetLastError();
+    const int g = p.Hq / p.Hkv;
+    if (d == 128 && block_m == 128 && (g & 1) == 0) {
+        static bool attr_set = false;  // opt in to more than 64 KB of LDS once per instantiation
+        if (!attr_set) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_pp_kernel<MODE>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, PP_LDS_BYTES) != hipSuccess)
+                return VFA_ERR_HIP;
+            attr_set = true;
+        }
+        const dim3 grid_pp((unsigned)(p.B * (p.Hq / 2) * p.Tr));
+        attn_fwd_pp_kernel<MODE><<<grid_pp, 512, PP_LDS_BYTES, s>>>(p);
+        return hipGetLastError() == hipSuccess ? VFA_OK : VFA_ERR_HIP;
+    }
+    const dim3 grid((unsigned)(p.B * p.Hq * p.Tr));
     if (d == 128 && block_m == 128) attn_fwd_kernel<128, 4, MODE><<<grid, 256, 0, s>>>(p);
     else if (d == 128 && block_m == 64) attn_fwd_kernel<128, 2, MODE><<<grid, 128, 0, s>>>(p);
     else if (d == 64 && block_m == 128) attn_fwd_kernel<64, 4, MODE><<<grid, 256, 0, s>>>(p);
