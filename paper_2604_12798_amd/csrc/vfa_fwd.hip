@@ -14,6 +14,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <math.h>
+#include <type_traits>
 
 #include "vfa.h"
 
@@ -172,44 +173,46 @@ __device__ __forceinline__ void qk_tile(const uint8_t* kt, const bf16x8* qf, f32
         }
 }
 
-// in-lane max of a score tile, entries with key index > limit excluded when MASKED
+// in-lane max of a score tile, entries with key index > limit excluded when MASKED.  The test is
+// written against rel = limit - key0 - 4*hh so that the per-entry side is a compile-time constant.
 template <bool MASKED>
 __device__ __forceinline__ float tile_rowmax(const f32x16* st, int key0, int limit, int hh) {
     float mx = -INFINITY;
+    const int rel = limit - key0 - 4 * hh;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int key = key0 + 32 * t + 8 * (r >> 2) + 4 * hh + (r & 3);
-            mx = fmaxf(mx, (!MASKED || key <= limit) ? st[t][r] : -INFINITY);
-        }
+        for (int r = 0; r < 16; ++r)
+            mx = fmaxf(mx, (!MASKED || 32 * t + 8 * (r >> 2) + (r & 3) <= rel) ? st[t][r] : -INFINITY);
     return mx;
 }
 
 // Softmax step of one tile for this lane's query: st (raw scores) -> pk (exp, bf16 pairs),
 // lsum += row sum.  SPECIAL: exact online-softmax update of m2 with rescale of lsum and ot;
 // otherwise m2 is frozen: no row max, no rescale (Alg. 1 / Table 1).
-template <bool SPECIAL, bool MASKED, int DB>
+// RESCALE = false is for the first visited tile, whose accumulators are still zero.  With MASKED the
+// caller may pass limit = INT_MAX for a tile that needs no masking (one code path, no branch).
+template <bool SPECIAL, bool MASKED, int DB, bool RESCALE = true>
 __device__ __forceinline__ void softmax_tile(f32x16* st, uint32_t* pk, f32x16* ot, float& m2, float& lsum, float c,
                                              int key0, int limit, int hh) {
     if (MASKED) {
+        const int rel = limit - key0 - 4 * hh;
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int key = key0 + 32 * t + 8 * (r >> 2) + 4 * hh + (r & 3);
-                st[t][r] = key <= limit ? st[t][r] : -INFINITY;
-            }
+            for (int r = 0; r < 16; ++r) st[t][r] = (32 * t + 8 * (r >> 2) + (r & 3) <= rel) ? st[t][r] : -INFINITY;
     }
     float msub = m2;
     if (SPECIAL) {
         const float mx = tile_rowmax<false>(st, 0, 0, hh);
         const float m_new = fmaxf(m2, xhalf_max(mx) * c);
         msub = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m2 - msub);
-        lsum *= alpha;
+        if (RESCALE) {
+            const float alpha = __builtin_amdgcn_exp2f(m2 - msub);
+            lsum *= alpha;
 #pragma unroll
-        for (int db = 0; db < DB; ++db) ot[db] *= alpha;
+            for (int db = 0; db < DB; ++db) ot[db] *= alpha;
+        }
         m2 = m_new;
     }
 #pragma unroll
@@ -222,17 +225,6 @@ __device__ __forceinline__ void softmax_tile(f32x16* st, uint32_t* pk, f32x16* o
             lsum += p1;
             pk[8 * t + (r >> 1)] = pack_bf16(p0, p1);
         }
-}
-
-__device__ __forceinline__ void softmax_dispatch4(bool special, bool masked, f32x16* st, uint32_t* pk, f32x16* ot,
-                                                  float& m2, float& lsum, float c, int key0, int limit, int hh) {
-    if (special) {
-        if (masked) softmax_tile<true, true, 4>(st, pk, ot, m2, lsum, c, key0, limit, hh);
-        else softmax_tile<true, false, 4>(st, pk, ot, m2, lsum, c, key0, limit, hh);
-    } else {
-        if (masked) softmax_tile<false, true, 4>(st, pk, ot, m2, lsum, c, key0, limit, hh);
-        else softmax_tile<false, false, 4>(st, pk, ot, m2, lsum, c, key0, limit, hh);
-    }
 }
 
 // O^T += V^T P^T for one tile.  P^T fragment of key chunk c (16 keys) = registers 8*(c&1)..+7 of
@@ -536,17 +528,54 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
     uint32_t pk[16];
     bool pv_pending = false;  // pk holds a tile whose P.V has not been accumulated yet
 
-    auto issue = [&](int k) {  // tile of visit k -> ring slot k & 3
-        const int j = vis.tile(k);
-        load_tile<D, NWV>(Kg, j * BN, N, Ks + (k & 3) * T::BYTES, false, wave, lane);
-        load_tile<D, NWV>(Vg, j * BN, N, Vs + (k & 3) * T::BYTES, true, wave, lane);
+    // ---- LDS-direct tile loads.  Per-lane byte offsets inside a tile are fixed for the whole kernel
+    // (rows 4*(8u + wave) + lane/16, swizzled chunk), so a full tile costs one scalar base per matrix
+    // and four load instructions per wave.  A ragged last tile clamps its rows and takes the slow path.
+    uint32_t offK[2], offV[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int r = 4 * (u * NWV + wave) + (lane >> 4), cp = lane & 15;
+        offK[u] = r * T::ROWB + ((cp ^ (r & 15)) << 4);
+        offV[u] = r * T::ROWB + ((cp ^ ((r & 3) << 2)) << 4);
+    }
+    auto dma16 = [&](const uint16_t* base, uint32_t off, uint8_t* dst) __attribute__((always_inline)) {
+        const uint32_t lds_addr =
+            __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)dst);
+        const uint64_t b64 = (uint64_t)(uintptr_t)base;  // wave-uniform by construction; tell the compiler
+        // (readfirstlane returns a signed int: go through uint32_t so the low half is not sign-extended)
+        const uint32_t b_lo = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)b64);
+        const uint32_t b_hi = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(b64 >> 32));
+        const uint64_t sbase = ((uint64_t)b_hi << 32) | (uint64_t)b_lo;
+        uint32_t m0_save;
+        asm volatile(
+            "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
+            : "=&s"(m0_save)
+            : "s"(lds_addr), "v"(off), "s"(sbase)
+            : "memory");
     };
-    auto tile_masked = [&](int j) { return (p.causal && j * BN + BN - 1 > row0) || (j + 1) * BN > N; };
+    auto issue = [&](int k) __attribute__((always_inline)) {  // tile of visit k -> ring slot k & 3 (this wave's 2 + 2 instructions)
+        const int j = vis.tile(k);
+        uint8_t* kd = Ks + (k & 3) * T::BYTES;
+        uint8_t* vd = Vs + (k & 3) * T::BYTES;
+        if (j * BN + BN <= N) {
+            const uint16_t* kb = Kg + (size_t)j * BN * D;
+            const uint16_t* vb = Vg + (size_t)j * BN * D;
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                dma16(kb, offK[u], kd + (u * NWV + wave) * 1024);
+                dma16(vb, offV[u], vd + (u * NWV + wave) * 1024);
+            }
+        } else {
+            load_tile<D, NWV>(Kg, j * BN, N, kd, false, wave, lane);
+            load_tile<D, NWV>(Vg, j * BN, N, vd, true, wave, lane);
+        }
+    };
+    auto tile_masked = [&](int j) __attribute__((always_inline)) { return (p.causal && j * BN + BN - 1 > row0) || (j + 1) * BN > N; };
 
     // ---- fragment loaders.  ld_v: the 4 V^T fragments (db = 0..3) of key chunk c; ld_k: the 4 K
     // fragments (kk, t) = (2*kk2, 0), (2*kk2, 1), (2*kk2+1, 0), (2*kk2+1, 1).
     const int kbase = T::k_base(ql, hh), vbase = T::v_base(lane, hh);
-    auto ld_v = [&](bf16x8* f, const uint8_t* vt, int c) {
+    auto ld_v = [&](bf16x8* f, const uint8_t* vt, int c) __attribute__((always_inline)) {
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
             const uint8_t* a = vt + (vbase ^ (db << 6)) + 16 * c * T::ROWB;
@@ -558,20 +587,20 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
             f[db] = __builtin_bit_cast(bf16x8, aw);
         }
     };
-    auto ld_k = [&](bf16x8* f, const uint8_t* kt, int kk2) {
+    auto ld_k = [&](bf16x8* f, const uint8_t* kt, int kk2) __attribute__((always_inline)) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int kk = 2 * kk2 + (e >> 1), t = e & 1;
             f[e] = *reinterpret_cast<const bf16x8*>(kt + (kbase ^ (kk << 5)) + t * 32 * T::ROWB);
         }
     };
-    auto pv4 = [&](const bf16x8* f, int c) {
+    auto pv4 = [&](const bf16x8* f, int c) __attribute__((always_inline)) {
         const u32x4 pw = {pk[4 * c], pk[4 * c + 1], pk[4 * c + 2], pk[4 * c + 3]};
         const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
 #pragma unroll
         for (int db = 0; db < DB; ++db) ot[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[db], pf, ot[db], 0, 0, 0);
     };
-    auto qk4 = [&](const bf16x8* f, int kk2) {
+    auto qk4 = [&](const bf16x8* f, int kk2) __attribute__((always_inline)) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int kk = 2 * kk2 + (e >> 1), t = e & 1;
@@ -580,15 +609,7 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
     };
     bf16x8 fa[4], fb[4];  // fragment double buffer of the matrix phase
 
-    auto issue_ahead = [&](int k) {  // at the start of matrix phase k: fetch visit k+2, make visit k+1 resident
-        if (k + 2 < nv) {
-            issue(k + 2);
-            __builtin_amdgcn_s_waitcnt(0x0F74);  // vmcnt(4): everything but the 4 loads just issued has landed
-        } else {
-            __builtin_amdgcn_s_waitcnt(0x0F70);
-        }
-    };
-    auto vote = [&](int k) {  // VSA: this wave's say on "skip the tile of visit k"
+    auto vote = [&](int k) __attribute__((always_inline)) {  // VSA: this wave's say on "skip the tile of visit k"
         const int j = vis.tile(k);
         const float mx = tile_masked(j) ? tile_rowmax<true>(st, j * BN, limit, hh) : tile_rowmax<false>(st, 0, 0, hh);
         const float mt2 = xhalf_max(mx) * p.c;
@@ -600,11 +621,10 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
 
     // Matrix phase of visit k in the steady state: P.V of visit k-1 (its chunk-0 fragments are already
     // in fa, fetched at the end of the vector phase), then Q.K^T of visit k.  Fragments for the next
-    // four MFMAs are read from LDS while the current four issue.
-    auto matrix_phase_full = [&](int k) {
+    // four MFMAs are read from LDS while the current four issue.  Nothing else is on this path.
+    auto matrix_phase_full = [&](int k) __attribute__((always_inline)) {
         const uint8_t* vt = Vs + ((k - 1) & 3) * T::BYTES;
         const uint8_t* kt = Ks + (k & 3) * T::BYTES;
-        issue_ahead(k);
         __builtin_amdgcn_s_setprio(1);
         st[0] = f32x16{0};
         st[1] = f32x16{0};
@@ -635,37 +655,104 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
         __builtin_amdgcn_s_setprio(0);
     };
     // Matrix phase without a pending P.V (first visit, or the previous tile was skipped): Q.K^T only.
-    auto matrix_phase_qk = [&](int k) {
-        issue_ahead(k);
+    auto matrix_phase_qk = [&](int k) __attribute__((always_inline)) {
         __builtin_amdgcn_s_setprio(1);
         qk_tile<D>(Ks + (k & 3) * T::BYTES, qf, st, ql, hh);
         if (MODE == MODE_VSA) vote(k);
         __builtin_amdgcn_s_setprio(0);
     };
-    // vector phase of visit k: softmax (or the skip decision) on the scores the matrix phase left in st
-    auto vector_phase = [&](int k) {
+    // Start of every vector phase: this wave's share of the tile 2 (group 0) or 3 (group 1) visits
+    // ahead goes into the ring slot whose last reader finished a phase ago, and the share issued one
+    // visit earlier is waited for, so that the barrier ending this phase publishes it in time:
+    // group 1 runs a phase late, hence fetches, and waits, one visit further ahead.
+    auto fetch_ahead = [&](int k) __attribute__((always_inline)) {
+        const int ki = k + 2 + grp;
+        if (ki < nv) {
+            issue(ki);
+            __builtin_amdgcn_s_waitcnt(0x0F74);  // vmcnt(4): all but the 4 loads just issued have landed
+        } else {
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+        }
+    };
+    // vector phase of visit k: softmax (or the skip decision) on the scores the matrix phase left in st.
+    // SPECIAL / FAST / FIRST are compile-time so that every loop below has exactly one softmax body:
+    // FAST = the tile needs no masking; FIRST = nothing accumulated yet (no rescale).
+    auto vector_phase = [&](int k, auto special_c, auto fast_c, auto first_c) __attribute__((always_inline)) {
+        constexpr bool SPECIAL = decltype(special_c)::value, FAST = decltype(fast_c)::value,
+                       FIRST = decltype(first_c)::value;
         const int j = vis.tile(k);
+        fetch_ahead(k);
         bool keep = true;
         if (MODE == MODE_VSA) {
-            keep = (votes[k & 1][grp][0] | votes[k & 1][grp][1] | votes[k & 1][grp][2] | votes[k & 1][grp][3]) != 0;
+            keep = __builtin_amdgcn_readfirstlane(votes[k & 1][grp][0] | votes[k & 1][grp][1] | votes[k & 1][grp][2] |
+                                                  votes[k & 1][grp][3]) != 0;  // same for every lane: say so
             if (mrow && (tid & 255) == 0) mrow[j] = keep ? 0 : 1;
         }
         pv_pending = keep;
         if (keep) {
-            softmax_dispatch4(k < vis.n_special, tile_masked(j), st, pk, ot, m2, lsum, p.c, j * BN, limit, hh);
+            if (FAST)
+                softmax_tile<SPECIAL, false, DB, !FIRST>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh);
+            else
+                softmax_tile<SPECIAL, true, DB, !FIRST>(st, pk, ot, m2, lsum, p.c, j * BN,
+                                                        tile_masked(j) ? limit : 0x3fffffff, hh);
             ld_v(fa, Vs + (k & 3) * T::BYTES, 0);  // first fragments of the coming P.V, in flight over the barrier
         }
     };
-
-    issue(0);
-    if (nv > 1) issue(1);
-    wait_vm0_and_sync();
-    if (grp == 1) __builtin_amdgcn_s_barrier();  // group 1 runs one phase behind group 0
-    for (int k = 0; k < nv; ++k) {
+    using std::false_type;
+    using std::true_type;
+    auto matrix_phase = [&](int k) __attribute__((always_inline)) {
         if (pv_pending) matrix_phase_full(k);
         else matrix_phase_qk(k);
+    };
+
+    // ---- prologue: visits 0 and 1 resident, group 1's share of visit 2 in flight
+    issue(0);
+    if (nv > 1) issue(1);
+    if (grp == 1 && nv > 2) {
+        issue(2);
+        __builtin_amdgcn_s_waitcnt(0x0F74);
+    } else {
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+    }
+    __syncthreads();
+    if (grp == 1) __builtin_amdgcn_s_barrier();  // group 1 runs one phase behind group 0
+
+    // Visits split into: visit 0 (no P.V pending, nothing to rescale); the remaining sink/local visits
+    // of VFA / VSA (exact-max update); a run of unmasked visits that all take one path (frozen max for
+    // VFA, exact-max for FA; VSA does not use it because its tiles may be skipped); and the trailing
+    // visits that may need masking (tiles on the diagonal or past the end of a ragged sequence).
+    constexpr bool TAIL_SPECIAL = (MODE == MODE_FA);
+    const int n_lead = (MODE == MODE_FA) ? 0 : vis.n_special;  // visits [0, n_lead) are sink/local
+    int k_fast_end = max(n_lead, 1);
+    if (MODE != MODE_VSA) {
+        int j_masked = p.causal ? a_lo : p.Tc;  // first tile index that needs masking
+        if (N % BN) j_masked = min(j_masked, p.Tc - 1);
+        int cnt = max(0, j_masked - vis.n1);  // visits of the ascending tail with tile index < j_masked
+        if (vis.n2 > 0) cnt -= max(0, min(j_masked, vis.s2 + vis.n2) - vis.s2);
+        k_fast_end = max(k_fast_end, min(nv, n_lead + cnt));
+    }
+    matrix_phase_qk(0);
+    __builtin_amdgcn_s_barrier();
+    if (MODE == MODE_FA || n_lead > 0) vector_phase(0, true_type{}, false_type{}, true_type{});
+    else vector_phase(0, false_type{}, false_type{}, true_type{});
+    __builtin_amdgcn_s_barrier();
+    int k = 1;
+    for (; k < min(n_lead, nv); ++k) {
+        matrix_phase(k);
         __builtin_amdgcn_s_barrier();
-        vector_phase(k);
+        vector_phase(k, true_type{}, false_type{}, false_type{});
+        __builtin_amdgcn_s_barrier();
+    }
+    for (; k < k_fast_end; ++k) {
+        matrix_phase_full(k);
+        __builtin_amdgcn_s_barrier();
+        vector_phase(k, std::integral_constant<bool, TAIL_SPECIAL>{}, true_type{}, false_type{});
+        __builtin_amdgcn_s_barrier();
+    }
+    for (; k < nv; ++k) {
+        matrix_phase(k);
+        __builtin_amdgcn_s_barrier();
+        vector_phase(k, std::integral_constant<bool, TAIL_SPECIAL>{}, false_type{}, false_type{});
         __builtin_amdgcn_s_barrier();
     }
     if (pv_pending) {  // drain the last P.V
