@@ -428,9 +428,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const Params p) {
 // One workgroup = 8 waves = two groups of 4; group G handles query head 2*hp + G of the same KV
 // head at the same query block, so both groups walk the same K/V tile sequence and every tile is
 // fetched once for 256 query rows.  The two waves that share a SIMD belong to different groups
-// and run one phase apart: while one issues MFMAs (P.V of the previous tile, then Q.K^T of the
-// current one) the other runs its softmax on the vector ALU.  Workgroup barriers mark the phase
-// boundaries and keep the stagger.  K/V tiles sit in a 4-deep LDS ring filled two tiles ahead.
+// and run half an interval apart: while one issues MFMAs (P.V of the previous tile, then Q.K^T of
+// the current one) the other runs its softmax on the vector ALU.  One workgroup barrier per tile
+// re-establishes the stagger and hands LDS ring slots over.  K/V tiles sit in a 4-deep LDS ring
+// filled two tiles ahead.
 constexpr int PP_STAGES = 4;
 constexpr int PP_LDS_BYTES = 2 * PP_STAGES * Tile<128>::BYTES;
 
@@ -661,10 +662,11 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
         if (MODE == MODE_VSA) vote(k);
         __builtin_amdgcn_s_setprio(0);
     };
-    // Start of every vector phase: this wave's share of the tile 2 (group 0) or 3 (group 1) visits
-    // ahead goes into the ring slot whose last reader finished a phase ago, and the share issued one
-    // visit earlier is waited for, so that the barrier ending this phase publishes it in time:
-    // group 1 runs a phase late, hence fetches, and waits, one visit further ahead.
+    // Start of every vector phase: this wave's share of the tile that matrix phases will reach two
+    // intervals from now goes into the ring slot whose last readers finished before the previous
+    // barrier, and the share issued one interval earlier is waited for, so that the barrier ending this
+    // interval publishes it one full interval before its first use.  Group 1's vector phase kv sits
+    // in the same interval as group 0's kv + 1, hence the "+ grp".
     auto fetch_ahead = [&](int k) __attribute__((always_inline)) {
         const int ki = k + 2 + grp;
         if (ki < nv) {
@@ -700,10 +702,6 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
     };
     using std::false_type;
     using std::true_type;
-    auto matrix_phase = [&](int k) __attribute__((always_inline)) {
-        if (pv_pending) matrix_phase_full(k);
-        else matrix_phase_qk(k);
-    };
 
     // ---- prologue: visits 0 and 1 resident, group 1's share of visit 2 in flight
     issue(0);
@@ -715,7 +713,6 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
         __builtin_amdgcn_s_waitcnt(0x0F70);
     }
     __syncthreads();
-    if (grp == 1) __builtin_amdgcn_s_barrier();  // group 1 runs one phase behind group 0
 
     // Visits split into: visit 0 (no P.V pending, nothing to rescale); the remaining sink/local visits
     // of VFA / VSA (exact-max update); a run of unmasked visits that all take one path (frozen max for
@@ -731,41 +728,70 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
         if (vis.n2 > 0) cnt -= max(0, min(j_masked, vis.s2 + vis.n2) - vis.s2);
         k_fast_end = max(k_fast_end, min(nv, n_lead + cnt));
     }
-    matrix_phase_qk(0);
-    __builtin_amdgcn_s_barrier();
-    if (MODE == MODE_FA || n_lead > 0) vector_phase(0, true_type{}, false_type{}, true_type{});
-    else vector_phase(0, false_type{}, false_type{}, true_type{});
-    __builtin_amdgcn_s_barrier();
-    int k = 1;
-    for (; k < min(n_lead, nv); ++k) {
-        matrix_phase(k);
-        __builtin_amdgcn_s_barrier();
-        vector_phase(k, true_type{}, false_type{}, false_type{});
-        __builtin_amdgcn_s_barrier();
-    }
-    for (; k < k_fast_end; ++k) {
-        matrix_phase_full(k);
-        __builtin_amdgcn_s_barrier();
-        vector_phase(k, std::integral_constant<bool, TAIL_SPECIAL>{}, true_type{}, false_type{});
-        __builtin_amdgcn_s_barrier();
-    }
-    for (; k < nv; ++k) {
-        matrix_phase(k);
-        __builtin_amdgcn_s_barrier();
-        vector_phase(k, std::integral_constant<bool, TAIL_SPECIAL>{}, false_type{}, false_type{});
-        __builtin_amdgcn_s_barrier();
-    }
-    if (pv_pending) {  // drain the last P.V
-        const uint8_t* vt = Vs + ((nv - 1) & 3) * T::BYTES;
-        pv4(fa, 0);
+    auto drain = [&]() __attribute__((always_inline)) {  // the P.V of the last visit
+        if (pv_pending) {
+            const uint8_t* vt = Vs + ((nv - 1) & 3) * T::BYTES;
+            pv4(fa, 0);
 #pragma unroll
-        for (int c = 1; c < 4; ++c) {
-            ld_v(fb, vt, c);
-            pv4(fb, c);
+            for (int c = 1; c < 4; ++c) {
+                ld_v(fb, vt, c);
+                pv4(fb, c);
+            }
         }
-    }
-    if (grp == 0) __builtin_amdgcn_s_barrier();
-    store_output<D>(p, ot, m2, lsum, b, h, qrow, hh);
+    };
+    // k may equal nv for group 1 (the matrix phase that follows its last vector phase): the Q.K^T half
+    // then runs on whatever the ring slot holds and its scores are never used; only the P.V counts.
+    auto matrix_any = [&](int k) __attribute__((always_inline)) {
+        if (pv_pending) matrix_phase_full(k);
+        else matrix_phase_qk(k);
+    };
+    // One interval = the stretch between two workgroup barriers.  Group 0 runs matrix phase kv and then
+    // vector phase kv; group 1 runs vector phase kv and then matrix phase kv + 1.  So each interval
+    // starts with one group on the matrix cores and the other on the vector ALU, but neither waits for
+    // the other inside the interval: whichever group has MFMAs ready keeps the matrix pipe fed.
+    // The whole loop nest is instantiated once per group (GRP is a compile-time constant) so that each
+    // copy is straight-line code for the register allocator.
+    auto run_group = [&](auto grp_c) __attribute__((always_inline)) {
+        constexpr int GRP = decltype(grp_c)::value;
+        auto interval = [&](int kv, auto special_c, auto fast_c, auto first_c, auto steady_c) __attribute__((always_inline)) {
+            constexpr bool STEADY = decltype(steady_c)::value;
+            if (GRP == 0) {
+                if (STEADY) matrix_phase_full(kv);
+                else matrix_any(kv);
+            }
+            __builtin_amdgcn_sched_barrier(0);  // keep the two phases apart in the instruction stream
+            // VSA: group 0's vector phase reads the votes its own matrix phase has just written, so its
+            // two phases need a barrier between them (and group 1 must match it)
+            if (MODE == MODE_VSA && GRP == 0) __builtin_amdgcn_s_barrier();
+            vector_phase(kv, special_c, fast_c, first_c);
+            if (MODE == MODE_VSA && GRP == 1) __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            if (GRP == 1) {
+                if (STEADY) matrix_phase_full(kv + 1);
+                else matrix_any(kv + 1);
+            }
+            __builtin_amdgcn_s_barrier();
+        };
+        if (GRP == 1) {  // group 1 starts half an interval late
+            matrix_phase_qk(0);
+            __builtin_amdgcn_s_barrier();
+        }
+        if (MODE == MODE_FA || n_lead > 0) interval(0, true_type{}, false_type{}, true_type{}, false_type{});
+        else interval(0, false_type{}, false_type{}, true_type{}, false_type{});
+        int k = 1;
+        for (; k < min(n_lead, nv); ++k) interval(k, true_type{}, false_type{}, false_type{}, false_type{});
+        for (; k < k_fast_end; ++k)
+            interval(k, std::integral_constant<bool, TAIL_SPECIAL>{}, true_type{}, false_type{}, true_type{});
+        for (; k < nv; ++k)
+            interval(k, std::integral_constant<bool, TAIL_SPECIAL>{}, false_type{}, false_type{}, false_type{});
+        if (GRP == 0) {
+            drain();
+            __builtin_amdgcn_s_barrier();
+        }
+        store_output<D>(p, ot, m2, lsum, b, h, qrow, hh);  // inside the per-group copy: nothing merges after it
+    };
+    if (grp == 0) run_group(std::integral_constant<int, 0>{});
+    else run_group(std::integral_constant<int, 1>{});
 }
 
 // ---------------------------------------------------------------------------------------------
