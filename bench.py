@@ -24,6 +24,8 @@ sys.path.insert(0, ROOT)
 from paper_2604_12798_amd import workloads as wl  # noqa: E402
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
+# measured HBM bytes of one VFA attention launch: (FETCH_SIZE KiB * 1.954 + WRITE_SIZE KiB * 1.0) * 1024
+TRAFFIC_BYTES = {"cfg3": int((4.538e5 * 1.954 + 2.662e5) * 1024)}
 METRIC = "attn fwd TFLOP/s + % MFMA bf16 peak, VFA/VSA vs online-softmax baseline"
 
 
@@ -132,7 +134,8 @@ def main():
         ms_k = time_region(run_vfa_kernel_only, args.steps, args.warmup)
         out["roofline"] = {"bound": "mfma", "kernel": "attn_fwd_kernel<128,4,VFA>", "achieved": dense / ms_k / 1e9,
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": dense / ms_k / 1e9 / MFMA_BF16_PEAK_TFLOPS,
-                           "traffic": None, "ms_per_launch": ms_k,
+                           # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (profiles/attn_fwd_cfg3.md)
+                           "traffic": TRAFFIC_BYTES.get(w.name), "ms_per_launch": ms_k,
                            "executed_tile_tflops": executed_tile_flop(w) / ms_k / 1e9}
     if "summary" in only:
         ms_s = time_region(run_summary, args.steps, args.warmup)
