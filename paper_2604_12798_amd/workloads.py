@@ -104,8 +104,9 @@ CONFIGS = {
     "cfg3": Workload("cfg3", 2, 32, 8, 16384, 128, 128, 64, True),
     # non-causal m-init stress: planted maximum in a random middle block
     "cfg4": Workload("cfg4", 1, 16, 16, 32768, 128, 128, 64, False, kind="planted", F=0),
-    # block-sparse causal, heavier tail
-    "cfg5": Workload("cfg5", 1, 8, 8, 65536, 128, 128, 64, True, F=16, theta=4096.0),
+    # block-sparse causal: stronger sink and a wide positional spectrum whose logit bonus decays roughly
+    # with the log of the distance, so that the 8-nat skip test removes a graded share of far tiles
+    "cfg5": Workload("cfg5", 1, 8, 8, 65536, 128, 128, 64, True, beta=6.0, kappa=3.0, F=16, theta=4096.0, bump=12.0),
 }
 
 
