@@ -501,13 +501,19 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
         const uint16_t* Rg = p.Krepr + ((size_t)(b * p.Hkv + hkv) * p.Tc) * D;
         float mx = -INFINITY;
         const int n_sum_tiles = (j_hi + BN) / BN;
-        for (int ts = 0; ts < n_sum_tiles; ++ts) {
-            __syncthreads();
-            load_tile<D, NWV>(Rg, ts * BN, p.Tc, Ks, false, wave, lane);
+        // the whole K/V ring is free here: fetch up to 8 summary tiles (512 key blocks) at once, so the
+        // load latency is paid once per batch instead of once per tile
+        for (int t0 = 0; t0 < n_sum_tiles; t0 += 2 * PP_STAGES) {
+            const int nb = min(2 * PP_STAGES, n_sum_tiles - t0);
+            if (t0) __syncthreads();  // the previous batch's readers are done
+            for (int u = 0; u < nb; ++u)
+                load_tile<D, NWV>(Rg, (t0 + u) * BN, p.Tc, pp_smem + u * T::BYTES, false, wave, lane);
             wait_vm0_and_sync();
-            f32x16 st[2];
-            qk_tile<D>(Ks, qf, st, ql, hh);
-            mx = fmaxf(mx, tile_rowmax<true>(st, ts * BN, j_hi, hh));
+            for (int u = 0; u < nb; ++u) {
+                f32x16 st[2];
+                qk_tile<D>(pp_smem + u * T::BYTES, qf, st, ql, hh);
+                mx = fmaxf(mx, tile_rowmax<true>(st, (t0 + u) * BN, j_hi, hh));
+            }
         }
         m2 = xhalf_max(mx) * p.c;
         __syncthreads();
@@ -626,7 +632,8 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
     auto matrix_phase_full = [&](int k) __attribute__((always_inline)) {
         const uint8_t* vt = Vs + ((k - 1) & 3) * T::BYTES;
         const uint8_t* kt = Ks + (k & 3) * T::BYTES;
-        __builtin_amdgcn_s_setprio(1);
+        if (MODE != MODE_FA) __builtin_amdgcn_s_setprio(1);
+        else __builtin_amdgcn_s_setprio(0);  // (also keeps the phase a scheduling region of its own)
         st[0] = f32x16{0};
         st[1] = f32x16{0};
         ld_v(fb, vt, 1); pv4(fa, 0);
@@ -657,7 +664,8 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
     };
     // Matrix phase without a pending P.V (first visit, or the previous tile was skipped): Q.K^T only.
     auto matrix_phase_qk = [&](int k) __attribute__((always_inline)) {
-        __builtin_amdgcn_s_setprio(1);
+        if (MODE != MODE_FA) __builtin_amdgcn_s_setprio(1);
+        else __builtin_amdgcn_s_setprio(0);  // (also keeps the phase a scheduling region of its own)
         qk_tile<D>(Ks + (k & 3) * T::BYTES, qf, st, ql, hh);
         if (MODE == MODE_VSA) vote(k);
         __builtin_amdgcn_s_setprio(0);
@@ -683,6 +691,11 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
         constexpr bool SPECIAL = decltype(special_c)::value, FAST = decltype(fast_c)::value,
                        FIRST = decltype(first_c)::value;
         const int j = vis.tile(k);
+        // Which wave of a SIMD gets the issue slots first decides how well MFMA and vector work overlap:
+        // measured, the frozen-max modes do best with the matrix phase on top (its one issue per 32 cycles
+        // is never delayed), the exact-max baseline, whose vector phase is the longer one, with the
+        // vector phase on top.
+        if (MODE == MODE_FA) __builtin_amdgcn_s_setprio(2);
         fetch_ahead(k);
         bool keep = true;
         if (MODE == MODE_VSA) {
@@ -699,6 +712,7 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
                                                         tile_masked(j) ? limit : 0x3fffffff, hh);
             ld_v(fa, Vs + (k & 3) * T::BYTES, 0);  // first fragments of the coming P.V, in flight over the barrier
         }
+        if (MODE == MODE_FA) __builtin_amdgcn_s_setprio(0);
     };
     using std::false_type;
     using std::true_type;
