@@ -774,11 +774,7 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
                 else matrix_any(kv);
             }
             __builtin_amdgcn_sched_barrier(0);  // keep the two phases apart in the instruction stream
-            // VSA: group 0's vector phase reads the votes its own matrix phase has just written, so its
-            // two phases need a barrier between them (and group 1 must match it)
-            if (MODE == MODE_VSA && GRP == 0) __builtin_amdgcn_s_barrier();
             vector_phase(kv, special_c, fast_c, first_c);
-            if (MODE == MODE_VSA && GRP == 1) __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
             if (GRP == 1) {
                 if (STEADY) matrix_phase_full(kv + 1);
@@ -804,8 +800,35 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
         }
         store_output<D>(p, ot, m2, lsum, b, h, qrow, hh);  // inside the per-group copy: nothing merges after it
     };
-    if (grp == 0) run_group(std::integral_constant<int, 0>{});
-    else run_group(std::integral_constant<int, 1>{});
+    if constexpr (MODE == MODE_VSA) {
+        // VSA: a vector phase reads the votes that the matrix phase of the same visit wrote, so every
+        // phase boundary is a workgroup barrier; group 1 simply runs one phase behind group 0.
+        if (grp == 1) __builtin_amdgcn_s_barrier();
+        matrix_phase_qk(0);
+        __builtin_amdgcn_s_barrier();
+        if (n_lead > 0) vector_phase(0, true_type{}, false_type{}, true_type{});
+        else vector_phase(0, false_type{}, false_type{}, true_type{});
+        __builtin_amdgcn_s_barrier();
+        int k = 1;
+        for (; k < min(n_lead, nv); ++k) {
+            matrix_any(k);
+            __builtin_amdgcn_s_barrier();
+            vector_phase(k, true_type{}, false_type{}, false_type{});
+            __builtin_amdgcn_s_barrier();
+        }
+        for (; k < nv; ++k) {
+            matrix_any(k);
+            __builtin_amdgcn_s_barrier();
+            vector_phase(k, false_type{}, false_type{}, false_type{});
+            __builtin_amdgcn_s_barrier();
+        }
+        drain();
+        if (grp == 0) __builtin_amdgcn_s_barrier();
+        store_output<D>(p, ot, m2, lsum, b, h, qrow, hh);
+    } else {
+        if (grp == 0) run_group(std::integral_constant<int, 0>{});
+        else run_group(std::integral_constant<int, 1>{});
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
