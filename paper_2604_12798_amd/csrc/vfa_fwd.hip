@@ -253,6 +253,78 @@ __device__ __forceinline__ void pv_tile(const uint8_t* vt, const uint32_t* pk, f
     }
 }
 
+// Software-pipelined forms of qk_tile / pv_tile: the LDS reads for the next group of MFMAs are issued
+// before the current group, and the scheduler is told to keep that order (one read per MFMA slot).
+template <int D>
+__device__ __forceinline__ void qk_tile_pipe(const uint8_t* kt, const bf16x8* qf, f32x16* st, int ql, int hh) {
+    using T = Tile<D>;
+    constexpr int NG = D / 32;  // groups of 4 MFMAs: k-steps (2g, 2g+1) x key halves (0, 1)
+    const int kbase = T::k_base(ql, hh);
+    bf16x8 f[2][4];
+    auto ld = [&](bf16x8* dst, int g) __attribute__((always_inline)) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            dst[e] = *reinterpret_cast<const bf16x8*>(kt + (kbase ^ ((2 * g + (e >> 1)) << 5)) + (e & 1) * 32 * T::ROWB);
+    };
+    st[0] = f32x16{0};
+    st[1] = f32x16{0};
+    ld(f[0], 0);
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        if (g + 1 < NG) ld(f[(g + 1) & 1], g + 1);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            st[e & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[g & 1][e], qf[2 * g + (e >> 1)], st[e & 1], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+    for (int g = 0; g + 1 < NG; ++g)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        }
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+}
+
+template <int D>
+__device__ __forceinline__ void pv_tile_pipe(const uint8_t* vt, const uint32_t* pk, f32x16* ot, int lane, int hh) {
+    using T = Tile<D>;
+    constexpr int DB = D / 32;
+    const int vbase = T::v_base(lane, hh);
+    bf16x8 f[2][DB];
+    auto ld = [&](bf16x8* dst, int c) __attribute__((always_inline)) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            const uint8_t* a = vt + (vbase ^ (db << 6)) + 16 * c * T::ROWB;
+            const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(a));
+            const s16x4 v1 =
+                __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(a + 8 * T::ROWB));
+            const u32x2 a0 = __builtin_bit_cast(u32x2, v0), a1 = __builtin_bit_cast(u32x2, v1);
+            const u32x4 aw = {a0[0], a0[1], a1[0], a1[1]};
+            dst[db] = __builtin_bit_cast(bf16x8, aw);
+        }
+    };
+    ld(f[0], 0);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        if (c < 3) ld(f[(c + 1) & 1], c + 1);
+        const u32x4 pw = {pk[4 * c], pk[4 * c + 1], pk[4 * c + 2], pk[4 * c + 3]};
+        const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) ot[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[c & 1][db], pf, ot[db], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * DB, 0);
+#pragma unroll
+    for (int c = 0; c < 3; ++c)
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        }
+    __builtin_amdgcn_sched_group_barrier(0x008, DB, 0);
+}
+
 // O = O^T / l (bf16, round to nearest even), LSE = (m2 + log2 l) ln 2
 template <int D>
 __device__ __forceinline__ void store_output(const Params& p, const f32x16* ot, float m2, float lsum, int b, int h,
@@ -391,7 +463,11 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const Params p) {
         const bool special = k < vis.n_special;
         const bool masked = (p.causal && j * BN + BN - 1 > row0) || (j + 1) * BN > N;
         f32x16 st[2];
-        qk_tile<D>(Ks + buf * T::BYTES, qf, st, ql, hh);
+        // the wave that issues MFMAs gets the issue slots first; a wave of the other workgroup on this
+        // SIMD fills the gaps with its softmax
+        __builtin_amdgcn_s_setprio(1);
+        qk_tile_pipe<D>(Ks + buf * T::BYTES, qf, st, ql, hh);
+        __builtin_amdgcn_s_setprio(0);
         bool keep = true;
         if (MODE == MODE_VSA) {
             // block vote: skip iff every row of the query block has m~ < m - threshold
@@ -416,7 +492,9 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const Params p) {
                 if (masked) softmax_tile<false, true, DB>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh);
                 else softmax_tile<false, false, DB>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh);
             }
-            pv_tile<D>(Vs + buf * T::BYTES, pk, ot, lane, hh);
+            __builtin_amdgcn_s_setprio(1);
+            pv_tile_pipe<D>(Vs + buf * T::BYTES, pk, ot, lane, hh);
+            __builtin_amdgcn_s_setprio(0);
         }
         wait_vm0_and_sync();
     }
