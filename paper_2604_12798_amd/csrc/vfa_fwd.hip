@@ -623,36 +623,40 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
         offK[u] = r * T::ROWB + ((cp ^ (r & 15)) << 4);
         offV[u] = r * T::ROWB + ((cp ^ ((r & 3) << 2)) << 4);
     }
-    auto dma16 = [&](const uint16_t* base, uint32_t off, uint8_t* dst) __attribute__((always_inline)) {
-        const uint32_t lds_addr =
-            __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)dst);
-        const uint64_t b64 = (uint64_t)(uintptr_t)base;  // wave-uniform by construction; tell the compiler
+    // LDS byte address of this wave's first 1 KiB piece of ring slot 0 (K ring; the V ring sits
+    // PP_STAGES tiles further), as an integer: address arithmetic below stays on the scalar unit
+    const uint32_t lds_k0 = __builtin_amdgcn_readfirstlane(
+        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)(Ks + wave * 1024));
+    auto uniform64 = [&](const uint16_t* ptr) __attribute__((always_inline)) {  // tell the compiler the pointer is wave-uniform
+        const uint64_t b64 = (uint64_t)(uintptr_t)ptr;
         // (readfirstlane returns a signed int: go through uint32_t so the low half is not sign-extended)
         const uint32_t b_lo = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)b64);
         const uint32_t b_hi = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(b64 >> 32));
-        const uint64_t sbase = ((uint64_t)b_hi << 32) | (uint64_t)b_lo;
-        uint32_t m0_save;
-        asm volatile(
-            "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
-            : "=&s"(m0_save)
-            : "s"(lds_addr), "v"(off), "s"(sbase)
-            : "memory");
+        return ((uint64_t)b_hi << 32) | (uint64_t)b_lo;
     };
     auto issue = [&](int k) __attribute__((always_inline)) {  // tile of visit k -> ring slot k & 3 (this wave's 2 + 2 instructions)
         const int j = vis.tile(k);
-        uint8_t* kd = Ks + (k & 3) * T::BYTES;
-        uint8_t* vd = Vs + (k & 3) * T::BYTES;
         if (j * BN + BN <= N) {
-            const uint16_t* kb = Kg + (size_t)j * BN * D;
-            const uint16_t* vb = Vg + (size_t)j * BN * D;
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                dma16(kb, offK[u], kd + (u * NWV + wave) * 1024);
-                dma16(vb, offV[u], vd + (u * NWV + wave) * 1024);
-            }
+            // one asm block for the four loads: M0 (the LDS base of an LDS-direct load) is saved once and
+            // restored at the end; pieces u = 0, 1 of a tile are 8 KiB apart in LDS
+            const uint64_t kb = uniform64(Kg + (size_t)j * BN * D), vb = uniform64(Vg + (size_t)j * BN * D);
+            const uint32_t lk0 = lds_k0 + (k & 3) * T::BYTES, lk1 = lk0 + NWV * 1024;
+            const uint32_t lv0 = lk0 + PP_STAGES * T::BYTES, lv1 = lv0 + NWV * 1024;
+            uint32_t m0_save;
+            asm volatile(
+                "s_mov_b32 %0, m0\n\t"
+                "s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %5, %9\n\t"
+                "s_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %7, %10\n\t"
+                "s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %6, %9\n\t"
+                "s_mov_b32 m0, %4\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %8, %10\n\t"
+                "s_mov_b32 m0, %0"
+                : "=&s"(m0_save)
+                : "s"(lk0), "s"(lk1), "s"(lv0), "s"(lv1), "v"(offK[0]), "v"(offK[1]), "v"(offV[0]), "v"(offV[1]), "s"(kb),
+                  "s"(vb)
+                : "memory");
         } else {
-            load_tile<D, NWV>(Kg, j * BN, N, kd, false, wave, lane);
-            load_tile<D, NWV>(Vg, j * BN, N, vd, true, wave, lane);
+            load_tile<D, NWV>(Kg, j * BN, N, Ks + (k & 3) * T::BYTES, false, wave, lane);
+            load_tile<D, NWV>(Vg, j * BN, N, Vs + (k & 3) * T::BYTES, true, wave, lane);
         }
     };
     auto tile_masked = [&](int j) __attribute__((always_inline)) { return (p.causal && j * BN + BN - 1 > row0) || (j + 1) * BN > N; };
