@@ -94,14 +94,11 @@ __device__ inline uint32_t pack_bf16(float a, float b) {
 // remaining visible tiles ascending.  The first n_special visits take the exact-max update.
 struct Visit {
     int n1, s2, n2, total, n_special;
-    __device__ int tile(int k) const {
-        if (k < n1) return k;
-        k -= n1;
-        if (k < n2) return s2 + k;
-        k -= n2;
-        int j = n1 + k;
-        if (n2 > 0 && j >= s2) j += n2;
-        return j;
+    __device__ int tile(int k) const {  // branch-free: this sits on the scalar unit in front of every tile fetch
+        const int lead = k < n1 ? k : s2 + (k - n1);
+        int tail = k - n2;                                  // = n1 + (k - n1 - n2)
+        tail += (n2 > 0 && tail >= s2) ? n2 : 0;
+        return k < n1 + n2 ? lead : tail;
     }
 };
 
