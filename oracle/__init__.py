@@ -146,6 +146,25 @@ def blocks(Q, K, V, block_m, block_n, causal, blocks, *, n_sink=1, n_local=1, us
     return out
 
 
+def fa_lazy(Q, K, V, block_m, block_n, causal, blocks_, tau, scale=None):
+    """Online softmax whose rows keep their old max while it grows by at most tau*ln2 (the
+    rescale-skip stage of the Blasst_FA4 variant).  Returns dict O, LSE, counters
+    (tiles visited, rowmax executions, tiles whose rescale ran, 0)."""
+    Q, K, V = _f32(Q), _f32(K), _f32(V)
+    B, Hq, Hkv, N, d = _dims(Q, K)
+    scale = 1.0 / math.sqrt(d) if scale is None else scale
+    blk = np.ascontiguousarray(blocks_, dtype=np.int32)
+    n = len(blk)
+    O = np.full((n, block_m, d), np.nan); L = np.full((n, block_m), np.nan)
+    cnt = np.zeros((n, 4), dtype=np.int64)
+    rc = _load().oracle_fa_lazy(
+        _p(Q, ctypes.c_float), _p(K, ctypes.c_float), _p(V, ctypes.c_float), B, Hq, Hkv, N, d,
+        block_m, block_n, int(causal), ctypes.c_double(scale), ctypes.c_double(float(tau)), n,
+        _p(blk, ctypes.c_int), _p(O, ctypes.c_double), _p(L, ctypes.c_double), _p(cnt, ctypes.c_int64))
+    assert rc == 0
+    return dict(O=O, LSE=L, counters=cnt)
+
+
 def fa2(Q, K, V, block_m, block_n, causal, blocks_, scale=None, want_traj=False):
     """FA column of Table 1: ascending order, exact-max update on every block."""
     return blocks(Q, K, V, block_m, block_n, causal, blocks_, n_sink=0, n_local=0, use_minit=False,

@@ -234,6 +234,7 @@ int oracle_visit_list(int N, int block_m, int block_n, int causal, int i, int n_
 typedef struct {
     int n_sink, n_local, use_minit, reorder, freeze, vsa;
     double ln_lambda;
+    double lazy_tau; /* < 0: off; else keep the old max while it grows by at most lazy_tau * ln 2 */
 } opts_t;
 
 static void one_block(const prob_t *p, const opts_t *o, const double *krepr, int b, int h, int i,
@@ -311,7 +312,21 @@ static void one_block(const prob_t *p, const opts_t *o, const double *krepr, int
             }
         }
         if (mask_row) mask_row[j] = 0;
-        if (special) counters[2] += 1; /* rescale chain executed on this tile */
+        if (special && o->lazy_tau >= 0.0) {
+            /* conditional rescale (the rescale-skip rule of the Blasst_FA4 variant): a row whose max
+             * grew by at most tau * ln 2 keeps its old max, so its scale factor is 1; the rescale chain
+             * of the tile counts as executed only if some row did change its max */
+            int any = 0;
+            for (int rr = 0; rr < nr; ++rr) {
+                const double m_new = fmax(m[rr], mt[rr]);
+                const int keep_old = (m[rr] != -INFINITY) && (m_new - m[rr] <= o->lazy_tau * 0.69314718055994530942);
+                if (keep_old) mt[rr] = -INFINITY; /* row takes max(m, -inf) = m below */
+                else if (m_new != m[rr]) any = 1;
+            }
+            counters[2] += any;
+        } else if (special) {
+            counters[2] += 1; /* rescale chain executed on this tile */
+        }
         for (int rr = 0; rr < nr; ++rr) {
             double m_use = m[rr], alpha = 1.0;
             if (special) {
@@ -373,7 +388,7 @@ int oracle_blocks(const float *Q, const float *K, const float *V, int B, int Hq,
     if (Hq % Hkv != 0 || block_m <= 0 || block_n <= 0) return -1;
     if (use_minit && !krepr && !m_override) return -1;
     prob_t p = {Q, K, V, B, Hq, Hkv, N, d, block_m, block_n, causal, scale};
-    opts_t o = {n_sink, n_local, use_minit, reorder, freeze, vsa, ln_lambda};
+    opts_t o = {n_sink, n_local, use_minit, reorder, freeze, vsa, ln_lambda, -1.0};
     const int Tc = ceil_div(N, block_n);
 #pragma omp parallel for schedule(dynamic, 1)
     for (int n = 0; n < nblk; ++n) {
@@ -387,6 +402,28 @@ int oracle_blocks(const float *Q, const float *K, const float *V, int B, int Hq,
                   mask_out ? mask_out + (size_t)n * Tc : NULL,
                   margin_out ? margin_out + (size_t)n * Tc : NULL, cn,
                   traj ? traj + (size_t)n * Tc * block_m * 2 : NULL);
+    }
+    return 0;
+}
+
+/* Online softmax with the conditional rescale of the "Blasst_FA4" variant (its second stage
+ * alone, no block skipping): ascending order, row max on every block, but a row adopts the
+ * new max only when it exceeds the old one by more than tau * ln 2; otherwise the old max is
+ * used and the row's scale factor is exactly 1.  The result is the exact attention output for
+ * any tau >= 0 (the max cancels in O / l); what changes is how often the rescale runs.
+ *   counters [nblk, 4]: tiles visited, rowmax executions, tiles whose rescale chain ran, 0   */
+int oracle_fa_lazy(const float *Q, const float *K, const float *V, int B, int Hq, int Hkv, int N,
+                   int d, int block_m, int block_n, int causal, double scale, double tau, int nblk,
+                   const int *blocks, double *O, double *LSE, int64_t *counters) {
+    if (Hq % Hkv != 0 || block_m <= 0 || block_n <= 0 || !(tau >= 0.0)) return -1;
+    prob_t p = {Q, K, V, B, Hq, Hkv, N, d, block_m, block_n, causal, scale};
+    opts_t o = {0, 0, 0, 0, 0, 0, 0.0, tau};
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int n = 0; n < nblk; ++n) {
+        int64_t *cn = counters + (size_t)n * 4;
+        cn[0] = cn[1] = cn[2] = cn[3] = 0;
+        one_block(&p, &o, NULL, blocks[3 * n], blocks[3 * n + 1], blocks[3 * n + 2], NULL,
+                  O + (size_t)n * block_m * d, LSE + (size_t)n * block_m, NULL, NULL, NULL, NULL, cn, NULL);
     }
     return 0;
 }

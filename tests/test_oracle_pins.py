@@ -292,6 +292,47 @@ def test_table1_op_counts(oracle):
         assert vfa[i, 0] == N // bn and vfa[i, 1] == vfa[i, 2] == n_special
 
 
+def test_lazy_rescale_is_exact_and_runs_the_rescale_less_often(oracle):
+    """Conditional rescale (appendix, Blasst_FA4 variant, second stage): any tau >= 0 gives the
+    exact output (the max cancels in O / l); tau = 0 is the FA column itself; the number of tiles
+    whose rescale chain runs falls as tau grows and is 1 once tau exceeds every score gap."""
+    N, d, bm, bn = 160, 6, 32, 16
+    Q, K, V = 3.0 * rnd(40, 1, 2, N, d), rnd(41, 1, 1, N, d), rnd(42, 1, 1, N, d)
+    blocks = np.array([(0, h, i) for h in range(2) for i in range(N // bm)], np.int32)
+    for causal in (False, True):
+        fa = oracle.fa2(Q, K, V, bm, bn, causal, blocks)
+        ex_O, ex_L, _ = oracle.exact(Q, K, V, bm, causal, blocks)
+        prev = None
+        for tau in (0.0, 0.5, 2.0, 8.0, 1e6):
+            out = oracle.fa_lazy(Q, K, V, bm, bn, causal, blocks, tau)
+            assert np.abs(out["O"] - ex_O).max() < 1e-12 and np.abs(out["LSE"] - ex_L).max() < 1e-12
+            c = out["counters"]
+            assert np.array_equal(c[:, 0], fa["counters"][:, 0]) and np.array_equal(c[:, 1], c[:, 0])
+            if tau == 0.0:
+                assert np.array_equal(out["O"], fa["O"]) and np.array_equal(out["LSE"], fa["LSE"])
+            if prev is not None:
+                assert (c[:, 2] <= prev).all()
+            prev = c[:, 2]
+        assert (prev == 1).all()   # only the first tile, where the max leaves -inf
+    # the rule itself, row by row on the full score matrix: which tiles change some row's max
+    tau = 2.0
+    for causal in (False, True):
+        got = oracle.fa_lazy(Q, K, V, bm, bn, causal, blocks, tau)["counters"][:, 2]
+        for n, (_, h, i) in enumerate(blocks):
+            S = (Q[0, h].astype(np.float64) @ K[0, 0].astype(np.float64).T) / math.sqrt(d)
+            if causal:
+                S = np.where(np.arange(N)[None, :] > np.arange(N)[:, None], -np.inf, S)
+            m = np.full(bm, -np.inf)
+            changed = 0
+            for j in range((i * bm + bm - 1) // bn + 1 if causal else N // bn):
+                mt = np.maximum(m, S[i * bm:(i + 1) * bm, j * bn:(j + 1) * bn].max(1))
+                adopt = (m == -np.inf) | (mt - m > tau * math.log(2))
+                new_m = np.where(adopt, mt, m)
+                changed += int((new_m != m).any())
+                m = new_m
+            assert got[n] == changed
+
+
 # ------------------------------------------------------------------ VSA
 def _vsa_problem(seed=30, N=256, d=8, causal=True):
     w = wl.small(wl.CONFIGS["cfg2"], B=1, Hq=2, Hkv=1, N=N, d=d, block_m=32, block_n=16, F=1, W=16.0, theta=4.0,
