@@ -5,8 +5,8 @@
 
 One step = one call of vfa_attn_fwd (key-block summary pre-pass + attention kernel) on the
 workload's whole batch, inputs resident in HBM.  The same K steps are also timed for
-fa_baseline_fwd (the online-softmax A/B kernel) and vsa_attn_fwd, and reported beside the
-headline.  Prints ONE JSON line.
+fa_baseline_fwd (the online-softmax A/B kernel), fa_lazy_rescale_fwd (the same with the rescale
+skipped while the row max grows by less than 2^8) and vsa_attn_fwd, and reported beside the headline.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -113,6 +113,9 @@ def main():
     def run_fa():
         vfa.fa_baseline_fwd(Q, K, V, **kw)
 
+    def run_fa_lazy():
+        vfa.fa_lazy_rescale_fwd(Q, K, V, rescale_tau=8.0, **kw)
+
     def run_vsa():
         vfa.vsa_attn_fwd(Q, K, V, use_minit=1, skip_threshold_nats=w.skip_threshold_nats, skip_mask=M, **vkw)
 
@@ -149,6 +152,9 @@ def main():
         out["baseline_fa"] = {"ms_per_step": ms_fa, "tflops": dense / ms_fa / 1e9,
                               "pct_mfma_bf16_peak": 100.0 * dense / ms_fa / 1e9 / MFMA_BF16_PEAK_TFLOPS}
         out["speedup_vfa_vs_fa"] = ms_fa / ms_vfa
+        ms_lz = time_region(run_fa_lazy, args.steps, args.warmup)   # second baseline: conditional rescale, tau = 8
+        out["baseline_fa_lazy_rescale"] = {"ms_per_step": ms_lz, "tflops": dense / ms_lz / 1e9, "rescale_tau": 8.0,
+                                           "speedup_vfa_vs_this": ms_lz / ms_vfa}
     if "vsa" in only:
         ms_vsa = time_region(run_vsa, args.steps, args.warmup)
         torch.cuda.synchronize()

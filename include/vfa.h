@@ -54,6 +54,20 @@ int fa_baseline_fwd(const void* Q, const void* K, const void* V, void* O, float*
                     int Hq, int Hkv, int N, int d, int block_m, int block_n, int causal,
                     float softmax_scale, void* stream);
 
+/* Online softmax with conditional rescale: the second comparison kernel (related work on
+ * FlashAttention-4, "conditionally eliding the output rescale"; appendix, variant Blasst_FA4,
+ * its rescale-skip rule without the block skipping).  As fa_baseline_fwd, except that a query
+ * row adopts the new running max only when it exceeds the old one by more than
+ * rescale_tau * ln 2 (rescale_tau >= 0, finite, in factors of two; 8 is the usual choice);
+ * otherwise the row keeps its old max, its scale factor is exactly 1, and when this holds for
+ * all 32 rows of a wave the rescale of l and O is not executed.  The output is the same exact
+ * attention (the max cancels in O / l); exp(S - m) may reach 2^rescale_tau.  With rescale_tau = 0
+ * every larger max is adopted, as in fa_baseline_fwd.  Same arguments, layouts and errors as
+ * fa_baseline_fwd; VFA_ERR_INVALID_ARG for a negative or non-finite rescale_tau. */
+int fa_lazy_rescale_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
+                        int Hq, int Hkv, int N, int d, int block_m, int block_n, int causal,
+                        float softmax_scale, float rescale_tau, void* stream);
+
 /* VFA forward (Alg. 1).  For each query block: the running max starts at
  * m_init = max_j scale * Q_i . Krepr_j over the visible key blocks (use_minit = 1: the summaries
  * are computed into `workspace` first; use_minit = 2: `workspace` already holds them, e.g. from

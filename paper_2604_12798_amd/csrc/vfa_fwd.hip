@@ -33,7 +33,9 @@ constexpr int BN = 64;  // keys per tile (= block_n)
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-enum Mode { MODE_FA = 0, MODE_VFA = 1, MODE_VSA = 2 };
+enum Mode { MODE_FA = 0, MODE_VFA = 1, MODE_VSA = 2, MODE_FA_LAZY = 3 };
+// the two online-softmax baselines: ascending order, row max on every tile, no summaries
+constexpr bool is_fa(int mode) { return mode == MODE_FA || mode == MODE_FA_LAZY; }
 
 struct Params {
     const uint16_t* Q;
@@ -47,6 +49,7 @@ struct Params {
     int causal, n_sink, n_local, use_minit;
     float c;     // softmax scale * log2(e)
     float thr2;  // skip threshold in log2 units
+    float tau2;  // MODE_FA_LAZY: a row keeps its old max while the new one exceeds it by at most tau2 (log2 units)
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -107,7 +110,7 @@ __device__ inline Visit make_visit(const Params& p, int a_lo, int a_hi, int j_hi
     Visit vis;
     vis.n1 = 0; vis.s2 = 0; vis.n2 = 0;
     vis.total = j_hi + 1;
-    if (MODE == MODE_FA) {
+    if (is_fa(MODE)) {
         vis.n_special = vis.total;
     } else {
         vis.n1 = min(p.n_sink, j_hi + 1);
@@ -189,9 +192,13 @@ __device__ __forceinline__ float tile_rowmax(const f32x16* st, int key0, int lim
 // otherwise m2 is frozen: no row max, no rescale (Alg. 1 / Table 1).
 // RESCALE = false is for the first visited tile, whose accumulators are still zero.  With MASKED the
 // caller may pass limit = INT_MAX for a tile that needs no masking (one code path, no branch).
-template <bool SPECIAL, bool MASKED, int DB, bool RESCALE = true>
+// LAZY (conditional rescale, with SPECIAL): a row adopts the new max only when it exceeds the old one by
+// more than tau2; otherwise it keeps the old max and its scale factor is exactly 1, and when that
+// holds for every row of the wave the whole rescale (lsum and the 16 * DB accumulator registers) is
+// branched over.  exp(S - m) may then reach 2^tau2, which bf16 / fp32 hold without trouble.
+template <bool SPECIAL, bool MASKED, int DB, bool RESCALE = true, bool LAZY = false>
 __device__ __forceinline__ void softmax_tile(f32x16* st, uint32_t* pk, f32x16* ot, float& m2, float& lsum, float c,
-                                             int key0, int limit, int hh) {
+                                             int key0, int limit, int hh, float tau2 = 0.f) {
     if (MASKED) {
         const int rel = limit - key0 - 4 * hh;
 #pragma unroll
@@ -202,9 +209,14 @@ __device__ __forceinline__ void softmax_tile(f32x16* st, uint32_t* pk, f32x16* o
     float msub = m2;
     if (SPECIAL) {
         const float mx = tile_rowmax<false>(st, 0, 0, hh);
-        const float m_new = fmaxf(m2, xhalf_max(mx) * c);
+        float m_new = fmaxf(m2, xhalf_max(mx) * c);
+        bool rescale = true;
+        if (LAZY) {
+            if (m2 != -INFINITY && m_new - m2 <= tau2) m_new = m2;
+            rescale = __builtin_amdgcn_ballot_w64(m_new != m2) != 0;  // wave-uniform
+        }
         msub = (m_new == -INFINITY) ? 0.f : m_new;
-        if (RESCALE) {
+        if (RESCALE && rescale) {
             const float alpha = __builtin_amdgcn_exp2f(m2 - msub);
             lsum *= alpha;
 #pragma unroll
@@ -415,7 +427,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const Params p) {
 
     // ---- m-initialisation: m2 = c * max_j Q_i . Krepr_j over visible key blocks (raw scores here)
     float m2 = -INFINITY;
-    if (MODE != MODE_FA && p.use_minit) {
+    if (!is_fa(MODE) && p.use_minit) {
         const uint16_t* Rg = p.Krepr + ((size_t)(b * p.Hkv + hkv) * p.Tc) * D;
         float mx = -INFINITY;
         const int n_sum_tiles = (j_hi + BN) / BN;
@@ -483,8 +495,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const Params p) {
         if (keep) {
             uint32_t pk[16];
             if (special) {
-                if (masked) softmax_tile<true, true, DB>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh);
-                else softmax_tile<true, false, DB>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh);
+                if (masked) softmax_tile<true, true, DB, true, MODE == MODE_FA_LAZY>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh, p.tau2);
+                else softmax_tile<true, false, DB, true, MODE == MODE_FA_LAZY>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh, p.tau2);
             } else {
                 if (masked) softmax_tile<false, true, DB>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh);
                 else softmax_tile<false, false, DB>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh);
@@ -572,7 +584,7 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
         qf[kk] = *reinterpret_cast<const bf16x8*>(Qg + (size_t)qrow_c * D + 16 * kk + 8 * hh);
 
     float m2 = -INFINITY;
-    if (MODE != MODE_FA && p.use_minit) {
+    if (!is_fa(MODE) && p.use_minit) {
         const uint16_t* Rg = p.Krepr + ((size_t)(b * p.Hkv + hkv) * p.Tc) * D;
         float mx = -INFINITY;
         const int n_sum_tiles = (j_hi + BN) / BN;
@@ -711,7 +723,7 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
     auto matrix_phase_full = [&](int k) __attribute__((always_inline)) {
         const uint8_t* vt = Vs + ((k - 1) & 3) * T::BYTES;
         const uint8_t* kt = Ks + (k & 3) * T::BYTES;
-        if (MODE != MODE_FA) __builtin_amdgcn_s_setprio(1);
+        if (!is_fa(MODE)) __builtin_amdgcn_s_setprio(1);
         else __builtin_amdgcn_s_setprio(0);  // (also keeps the phase a scheduling region of its own)
         st[0] = f32x16{0};
         st[1] = f32x16{0};
@@ -743,7 +755,7 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
     };
     // Matrix phase without a pending P.V (first visit, or the previous tile was skipped): Q.K^T only.
     auto matrix_phase_qk = [&](int k) __attribute__((always_inline)) {
-        if (MODE != MODE_FA) __builtin_amdgcn_s_setprio(1);
+        if (!is_fa(MODE)) __builtin_amdgcn_s_setprio(1);
         else __builtin_amdgcn_s_setprio(0);  // (also keeps the phase a scheduling region of its own)
         qk_tile<D>(Ks + (k & 3) * T::BYTES, qf, st, ql, hh);
         if (MODE == MODE_VSA) vote(k);
@@ -774,7 +786,7 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
         // measured, the frozen-max modes do best with the matrix phase on top (its one issue per 32 cycles
         // is never delayed), the exact-max baseline, whose vector phase is the longer one, with the
         // vector phase on top.
-        if (MODE == MODE_FA) __builtin_amdgcn_s_setprio(2);
+        if (is_fa(MODE)) __builtin_amdgcn_s_setprio(2);
         fetch_ahead(k);
         bool keep = true;
         if (MODE == MODE_VSA) {
@@ -785,13 +797,14 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
         pv_pending = keep;
         if (keep) {
             if (FAST)
-                softmax_tile<SPECIAL, false, DB, !FIRST>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh);
+                softmax_tile<SPECIAL, false, DB, !FIRST, MODE == MODE_FA_LAZY>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh,
+                                                                               p.tau2);
             else
-                softmax_tile<SPECIAL, true, DB, !FIRST>(st, pk, ot, m2, lsum, p.c, j * BN,
-                                                        tile_masked(j) ? limit : 0x3fffffff, hh);
+                softmax_tile<SPECIAL, true, DB, !FIRST, MODE == MODE_FA_LAZY>(st, pk, ot, m2, lsum, p.c, j * BN,
+                                                                              tile_masked(j) ? limit : 0x3fffffff, hh, p.tau2);
             ld_v(fa, Vs + (k & 3) * T::BYTES, 0);  // first fragments of the coming P.V, in flight over the barrier
         }
-        if (MODE == MODE_FA) __builtin_amdgcn_s_setprio(0);
+        if (is_fa(MODE)) __builtin_amdgcn_s_setprio(0);
     };
     using std::false_type;
     using std::true_type;
@@ -811,8 +824,8 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
     // of VFA / VSA (exact-max update); a run of unmasked visits that all take one path (frozen max for
     // VFA, exact-max for FA; VSA does not use it because its tiles may be skipped); and the trailing
     // visits that may need masking (tiles on the diagonal or past the end of a ragged sequence).
-    constexpr bool TAIL_SPECIAL = (MODE == MODE_FA);
-    const int n_lead = (MODE == MODE_FA) ? 0 : vis.n_special;  // visits [0, n_lead) are sink/local
+    constexpr bool TAIL_SPECIAL = is_fa(MODE);
+    const int n_lead = is_fa(MODE) ? 0 : vis.n_special;  // visits [0, n_lead) are sink/local
     int k_fast_end = max(n_lead, 1);
     if (MODE != MODE_VSA) {
         int j_masked = p.causal ? a_lo : p.Tc;  // first tile index that needs masking
@@ -865,7 +878,7 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
             matrix_phase_qk(0);
             __builtin_amdgcn_s_barrier();
         }
-        if (MODE == MODE_FA || n_lead > 0) interval(0, true_type{}, false_type{}, true_type{}, false_type{});
+        if (is_fa(MODE) || n_lead > 0) interval(0, true_type{}, false_type{}, true_type{}, false_type{});
         else interval(0, false_type{}, false_type{}, true_type{}, false_type{});
         int k = 1;
         for (; k < min(n_lead, nv); ++k) interval(k, true_type{}, false_type{}, false_type{}, false_type{});
@@ -1038,6 +1051,24 @@ int vfa_vsa_common(int mode, const void* Q, const void* K, const void* V, void* 
     return mode == MODE_VSA ? launch_fwd<MODE_VSA>(p, d, block_m, s) : launch_fwd<MODE_VFA>(p, d, block_m, s);
 }
 
+int fa_common(bool lazy, const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv,
+              int N, int d, int block_m, int block_n, int causal, float softmax_scale, float tau, void* stream) {
+    int rc = check_common(Q, K, V, O, LSE, B, Hq, Hkv, N, d, block_m, block_n);
+    if (rc != VFA_OK) return rc;
+    if (!isfinite(softmax_scale)) return VFA_ERR_INVALID_ARG;
+    if (B == 0 || N == 0) return VFA_OK;
+    Params p{};
+    p.Q = (const uint16_t*)Q; p.K = (const uint16_t*)K; p.V = (const uint16_t*)V;
+    p.O = (uint16_t*)O; p.LSE = LSE;
+    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N; p.Tr = ceil_div(N, block_m); p.Tc = ceil_div(N, block_n);
+    p.causal = causal ? 1 : 0;
+    const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)d);
+    p.c = scale * kLog2e;
+    p.tau2 = tau;  // tau is already a count of factors of two: tau * ln 2 nats = tau in the log2 domain
+    return lazy ? launch_fwd<MODE_FA_LAZY>(p, d, block_m, (hipStream_t)stream)
+                : launch_fwd<MODE_FA>(p, d, block_m, (hipStream_t)stream);
+}
+
 }  // namespace
 
 extern "C" {
@@ -1059,18 +1090,15 @@ int vfa_kblock_summary(const void* K, void* Krepr, int B, int Hkv, int N, int d,
 
 int fa_baseline_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int N,
                     int d, int block_m, int block_n, int causal, float softmax_scale, void* stream) {
-    int rc = check_common(Q, K, V, O, LSE, B, Hq, Hkv, N, d, block_m, block_n);
-    if (rc != VFA_OK) return rc;
-    if (!isfinite(softmax_scale)) return VFA_ERR_INVALID_ARG;
-    if (B == 0 || N == 0) return VFA_OK;
-    Params p{};
-    p.Q = (const uint16_t*)Q; p.K = (const uint16_t*)K; p.V = (const uint16_t*)V;
-    p.O = (uint16_t*)O; p.LSE = LSE;
-    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N; p.Tr = ceil_div(N, block_m); p.Tc = ceil_div(N, block_n);
-    p.causal = causal ? 1 : 0;
-    const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)d);
-    p.c = scale * kLog2e;
-    return launch_fwd<MODE_FA>(p, d, block_m, (hipStream_t)stream);
+    return fa_common(false, Q, K, V, O, LSE, B, Hq, Hkv, N, d, block_m, block_n, causal, softmax_scale, 0.f, stream);
+}
+
+int fa_lazy_rescale_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv,
+                        int N, int d, int block_m, int block_n, int causal, float softmax_scale, float rescale_tau,
+                        void* stream) {
+    if (!(rescale_tau >= 0.f && isfinite(rescale_tau))) return VFA_ERR_INVALID_ARG;
+    return fa_common(true, Q, K, V, O, LSE, B, Hq, Hkv, N, d, block_m, block_n, causal, softmax_scale, rescale_tau,
+                     stream);
 }
 
 int vfa_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int N,

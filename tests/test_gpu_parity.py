@@ -54,6 +54,10 @@ def _run_all(vfa, w, t, blocks, oracle, use_minit=True):
     res["fa"] = check_o_lse(O, L, Oe, Le, blocks, w.block_m, w.N, "fa_baseline_fwd vs exact")
     ref = oracle.fa2(Qh, Kh, Vh, w.block_m, w.block_n, w.causal, blocks)
     check_o_lse(O, L, ref["O"], ref["LSE"], blocks, w.block_m, w.N, "fa_baseline_fwd vs oracle FA")
+    for tau in (0.0, 8.0):   # conditional rescale: same exact attention for any tau (0: every new max is adopted)
+        O, L = vfa.fa_lazy_rescale_fwd(Q, K, V, rescale_tau=tau, **kw)
+        torch.cuda.synchronize()
+        res["fa_lazy%g" % tau] = check_o_lse(O, L, Oe, Le, blocks, w.block_m, w.N, "fa_lazy_rescale_fwd vs exact")
     O, L = vfa.vfa_attn_fwd(Q, K, V, n_sink=w.n_sink, n_local=w.n_local, use_minit=use_minit, **kw)
     torch.cuda.synchronize()
     ref = oracle.blocks(Qh, Kh, Vh, w.block_m, w.block_n, w.causal, blocks, n_sink=w.n_sink, n_local=w.n_local,
