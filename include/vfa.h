@@ -48,6 +48,13 @@ size_t vfa_workspace_bytes(int B, int Hkv, int N, int d, int block_n);
 int vfa_kblock_summary(const void* K, void* Krepr, int B, int Hkv, int N, int d, int block_n,
                        void* stream);
 
+/* The same pre-pass with the block representations of the k_repr ablation (Experiments, "Ablating
+ * the k_repr construction"): repr_mode 0 = sabsmax (as above), 1 = per-dimension maximum,
+ * 2 = per-dimension mean (fp32 sum, rounded to bf16), 3 = per-dimension largest magnitude without
+ * its sign.  VFA_ERR_INVALID_ARG for any other mode. */
+int vfa_kblock_summary_mode(const void* K, void* Krepr, int B, int Hkv, int N, int d, int block_n,
+                            int repr_mode, void* stream);
+
 /* Conventional online-softmax forward (Table 1, FA column; Sec. 2.2 "Flash Attention"): key
  * blocks in ascending order, row max / rescale on every block.  The A/B comparison kernel. */
 int fa_baseline_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
@@ -94,6 +101,26 @@ int vsa_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LS
                  int Hkv, int N, int d, int block_m, int block_n, int causal, int n_sink,
                  int n_local, int use_minit, float softmax_scale, float skip_threshold_nats,
                  unsigned char* skip_mask, void* workspace, size_t workspace_bytes, void* stream);
+
+/* VFA / VSA with the switches of the ablation study and of the sparse-attention variants
+ * (Experiments: "Ablating the k_repr construction", "Removing m-initialization", "Ablating the
+ * reordered schedule"; appendix: variants Blasst and Blasst_SWA).  As vfa_attn_fwd / vsa_attn_fwd,
+ * plus:
+ *   repr_mode  block representation used when use_minit == 1 (see vfa_kblock_summary_mode)
+ *   reorder    1 = sink blocks, local blocks, then the rest (the method); 0 = ascending block
+ *              order, the sink / local blocks keeping the exact-max update where they come
+ *   freeze     1 = exact-max update on sink / local blocks only (the method); 0 = on every
+ *              block (then n_sink = n_local = 0 with use_minit = 0 is allowed)
+ *   skip_threshold_nats  0 = no block skipping (skip_mask ignored); > 0 = the Alg. 2 skip test.
+ * reorder = freeze = 1, repr_mode = 0 is exactly vfa_attn_fwd / vsa_attn_fwd.  Vanilla BLASST is
+ * (use_minit 0, reorder 0, freeze 0, threshold > 0); Blasst_SWA is the same with reorder 1.
+ * Every setting without skipping is exact attention; they differ in how far the frozen max sits
+ * from the true one, which is what the ablation measures.  These run on the generic kernel. */
+int vfa_variant_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
+                    int Hq, int Hkv, int N, int d, int block_m, int block_n, int causal,
+                    int n_sink, int n_local, int use_minit, int repr_mode, int reorder, int freeze,
+                    float softmax_scale, float skip_threshold_nats, unsigned char* skip_mask,
+                    void* workspace, size_t workspace_bytes, void* stream);
 
 /* Static string for a return code. */
 const char* vfa_strerror(int code);

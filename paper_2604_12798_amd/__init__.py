@@ -13,8 +13,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libvfa.so")
 _lib = None
 
-EXPORTS = ("vfa_workspace_bytes", "vfa_kblock_summary", "fa_baseline_fwd", "fa_lazy_rescale_fwd", "vfa_attn_fwd",
-           "vsa_attn_fwd", "vfa_strerror")
+EXPORTS = ("vfa_workspace_bytes", "vfa_kblock_summary", "vfa_kblock_summary_mode", "fa_baseline_fwd",
+           "fa_lazy_rescale_fwd", "vfa_attn_fwd", "vsa_attn_fwd", "vfa_variant_fwd", "vfa_strerror")
 
 
 class VfaError(RuntimeError):
@@ -35,6 +35,10 @@ def lib() -> ctypes.CDLL:
         L.vfa_workspace_bytes.argtypes = [i, i, i, i, i]
         L.vfa_kblock_summary.restype = i
         L.vfa_kblock_summary.argtypes = [vp, vp, i, i, i, i, i, vp]
+        L.vfa_kblock_summary_mode.restype = i
+        L.vfa_kblock_summary_mode.argtypes = [vp, vp, i, i, i, i, i, i, vp]
+        L.vfa_variant_fwd.restype = i
+        L.vfa_variant_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, i, i, i, i, i, f, f, vp, vp, sz, vp]
         L.fa_baseline_fwd.restype = i
         L.fa_baseline_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, f, vp]
         L.fa_lazy_rescale_fwd.restype = i
@@ -88,13 +92,17 @@ def _outputs(Q, out, lse, want_lse):
     return O, L
 
 
-def kblock_summary(K, block_n: int = 64, out=None, stream=None):
-    """Key-block summaries Krepr [B, Hkv, ceil(N/block_n), d] (bf16) of K [B, Hkv, N, d]."""
+def kblock_summary(K, block_n: int = 64, out=None, stream=None, repr_mode: int = 0):
+    """Key-block summaries Krepr [B, Hkv, ceil(N/block_n), d] (bf16) of K [B, Hkv, N, d].
+    repr_mode 0 = sabsmax (the method); 1 / 2 / 3 = per-dimension max / mean / unsigned absmax."""
     import torch
     B, Hkv, N, d = K.shape
     Tc = -(-N // block_n)
     R = torch.empty((B, Hkv, Tc, d), dtype=torch.bfloat16, device=K.device) if out is None else out
-    rc = lib().vfa_kblock_summary(_ptr(K), _ptr(R), B, Hkv, N, d, block_n, _stream(stream))
+    if repr_mode == 0:
+        rc = lib().vfa_kblock_summary(_ptr(K), _ptr(R), B, Hkv, N, d, block_n, _stream(stream))
+    else:
+        rc = lib().vfa_kblock_summary_mode(_ptr(K), _ptr(R), B, Hkv, N, d, block_n, int(repr_mode), _stream(stream))
     if rc != 0:
         raise VfaError(rc, "vfa_kblock_summary")
     return R
@@ -159,4 +167,24 @@ def vsa_attn_fwd(Q, K, V, *, block_m=128, block_n=64, causal=True, n_sink=1, n_l
                             float(skip_threshold_nats), _ptr(M), _ptr(ws), ws_bytes, _stream(stream))
     if rc != 0:
         raise VfaError(rc, "vsa_attn_fwd")
+    return O, L, M
+
+
+def vfa_variant_fwd(Q, K, V, *, block_m=128, block_n=64, causal=True, n_sink=1, n_local=1, use_minit=True, repr_mode=0,
+                    reorder=True, freeze=True, softmax_scale=0.0, skip_threshold_nats=0.0, skip_mask=None,
+                    workspace=None, out=None, lse=None, want_lse=True, stream=None):
+    """VFA / VSA with the ablation switches; returns (O, LSE, mask) with mask None when nothing is skipped."""
+    import torch
+    B, Hq, Hkv, N, d = _check_qkv(Q, K, V)
+    O, L = _outputs(Q, out, lse, want_lse)
+    ws, ws_bytes = _workspace(Q, K, block_n, workspace)
+    M = skip_mask
+    if M is None and skip_threshold_nats != 0.0:
+        M = torch.empty((B, Hq, -(-N // block_m), -(-N // block_n)), dtype=torch.uint8, device=Q.device)
+    rc = lib().vfa_variant_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(L), B, Hq, Hkv, N, d, block_m, block_n,
+                               int(bool(causal)), int(n_sink), int(n_local), int(use_minit), int(repr_mode),
+                               int(bool(reorder)), int(bool(freeze)), float(softmax_scale), float(skip_threshold_nats),
+                               _ptr(M), _ptr(ws), ws_bytes, _stream(stream))
+    if rc != 0:
+        raise VfaError(rc, "vfa_variant_fwd")
     return O, L, M

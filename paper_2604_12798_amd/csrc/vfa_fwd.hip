@@ -47,6 +47,8 @@ struct Params {
     uint8_t* mask;
     int B, Hq, Hkv, N, Tr, Tc;
     int causal, n_sink, n_local, use_minit;
+    int order_asc;    // ablation: visit key blocks in ascending order (sink / local blocks keep the exact-max update)
+    int all_special;  // ablation: exact-max update on every visited block
     float c;     // softmax scale * log2(e)
     float thr2;  // skip threshold in log2 units
     float tau2;  // MODE_FA_LAZY: a row keeps its old max while the new one exceeds it by at most tau2 (log2 units)
@@ -97,18 +99,21 @@ __device__ inline uint32_t pack_bf16(float a, float b) {
 // remaining visible tiles ascending.  The first n_special visits take the exact-max update.
 struct Visit {
     int n1, s2, n2, total, n_special;
+    int m1, ms2, mn2;  // ascending-order ablation: tiles [0, m1) and [ms2, ms2 + mn2) are the sink / local ones
     __device__ int tile(int k) const {  // branch-free: this sits on the scalar unit in front of every tile fetch
         const int lead = k < n1 ? k : s2 + (k - n1);
         int tail = k - n2;                                  // = n1 + (k - n1 - n2)
         tail += (n2 > 0 && tail >= s2) ? n2 : 0;
         return k < n1 + n2 ? lead : tail;
     }
+    __device__ bool special(int k) const { return k < n_special || k < m1 || (k >= ms2 && k < ms2 + mn2); }
 };
 
 template <int MODE>
 __device__ inline Visit make_visit(const Params& p, int a_lo, int a_hi, int j_hi) {
     Visit vis;
     vis.n1 = 0; vis.s2 = 0; vis.n2 = 0;
+    vis.m1 = 0; vis.ms2 = 0; vis.mn2 = 0;
     vis.total = j_hi + 1;
     if (is_fa(MODE)) {
         vis.n_special = vis.total;
@@ -119,6 +124,11 @@ __device__ inline Visit make_visit(const Params& p, int a_lo, int a_hi, int j_hi
             if (hi >= lo) { vis.s2 = lo; vis.n2 = hi - lo + 1; }
         }
         vis.n_special = vis.n1 + vis.n2;
+        if (p.order_asc) {  // same sink / local sets, but no block is moved to the front
+            vis.m1 = vis.n1; vis.ms2 = vis.s2; vis.mn2 = vis.n2;
+            vis.n1 = 0; vis.s2 = 0; vis.n2 = 0; vis.n_special = 0;
+        }
+        if (p.all_special) vis.n_special = vis.total;
     }
     return vis;
 }
@@ -469,7 +479,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const Params p) {
             load_tile<D, NW>(Kg, jn * BN, N, Ks + (buf ^ 1) * T::BYTES, false, wave, lane);
             load_tile<D, NW>(Vg, jn * BN, N, Vs + (buf ^ 1) * T::BYTES, true, wave, lane);
         }
-        const bool special = k < vis.n_special;
+        const bool special = vis.special(k);
         const bool masked = (p.causal && j * BN + BN - 1 > row0) || (j + 1) * BN > N;
         f32x16 st[2];
         // the wave that issues MFMAs gets the issue slots first; a wave of the other workgroup on this
@@ -964,6 +974,51 @@ __global__ __launch_bounds__(256) void kblock_summary_kernel(const uint16_t* __r
     }
 }
 
+// The three ablated block representations (ablation of the k_repr construction): per dimension the
+// maximum (mode 1), the mean (mode 2: fp32 sum in a fixed order, rounded to bf16) or the largest
+// magnitude without its sign (mode 3).  Not on the hot path: one thread per (row group, 8 dims).
+template <int D>
+__global__ __launch_bounds__(256) void kblock_summary_alt_kernel(const uint16_t* __restrict__ K, uint16_t* __restrict__ R,
+                                                                 int N, int Tc, int block_n, int mode) {
+    constexpr int CH = D / 8;
+    constexpr int RG = 256 / CH;
+    __shared__ float part[RG][D];
+    const int j = blockIdx.x, bh = blockIdx.y;
+    const int ch = threadIdx.x % CH, rg = threadIdx.x / CH;
+    const int c0 = j * block_n, c1 = min(N, c0 + block_n);
+    const uint16_t* base = K + (size_t)bh * N * D;
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = mode == 1 ? -INFINITY : 0.f;
+    for (int r = c0 + rg; r < c1; r += RG) {
+        const u32x4 x = *reinterpret_cast<const u32x4*>(base + (size_t)r * D + ch * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float v = __uint_as_float(((x[e >> 1] >> (16 * (e & 1))) & 0xffffu) << 16);
+            acc[e] = mode == 1 ? fmaxf(acc[e], v) : (mode == 2 ? acc[e] + v : fmaxf(acc[e], fabsf(v)));
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) part[rg][ch * 8 + e] = acc[e];
+    __syncthreads();
+    if (rg == 0) {
+        const int nrg = min(RG, c1 - c0);  // row groups that saw at least one row
+        uint32_t out[4];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float a = acc[e];
+            for (int q = 1; q < nrg; ++q) {
+                const float v = part[q][ch * 8 + e];
+                a = mode == 2 ? a + v : fmaxf(a, v);
+            }
+            if (mode == 2) a /= (float)(c1 - c0);
+            const uint32_t bits = pack_bf16(a, 0.f) & 0xffffu;
+            out[e >> 1] = (e & 1) ? (out[e >> 1] | (bits << 16)) : bits;
+        }
+        *reinterpret_cast<u32x4*>(R + ((size_t)bh * Tc + j) * D + ch * 8) = u32x4{out[0], out[1], out[2], out[3]};
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // host side
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -988,7 +1043,7 @@ template <int MODE>
 int launch_fwd(const Params& p, int d, int block_m, hipStream_t s) {
     (void)hipGetLastError();
     const int g = p.Hq / p.Hkv;
-    if (d == 128 && block_m == 128 && (g & 1) == 0) {
+    if (d == 128 && block_m == 128 && (g & 1) == 0 && !p.order_asc && !p.all_special) {
         static bool attr_set = false;  // opt in to more than 64 KB of LDS once per instantiation
         if (!attr_set) {
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_pp_kernel<MODE>),
@@ -1009,23 +1064,31 @@ int launch_fwd(const Params& p, int d, int block_m, hipStream_t s) {
     return hipGetLastError() == hipSuccess ? VFA_OK : VFA_ERR_HIP;
 }
 
-int summary_launch(const void* K, void* Krepr, int B, int Hkv, int N, int d, int block_n, hipStream_t s) {
+int summary_launch(const void* K, void* Krepr, int B, int Hkv, int N, int d, int block_n, int repr_mode, hipStream_t s) {
     const int Tc = ceil_div(N, block_n);
     const dim3 grid((unsigned)Tc, (unsigned)(B * Hkv));
+    const uint16_t* k = (const uint16_t*)K;
+    uint16_t* r = (uint16_t*)Krepr;
     (void)hipGetLastError();
-    if (d == 128) kblock_summary_kernel<128><<<grid, 256, 0, s>>>((const uint16_t*)K, (uint16_t*)Krepr, N, Tc, block_n);
-    else kblock_summary_kernel<64><<<grid, 256, 0, s>>>((const uint16_t*)K, (uint16_t*)Krepr, N, Tc, block_n);
+    if (repr_mode == 0) {
+        if (d == 128) kblock_summary_kernel<128><<<grid, 256, 0, s>>>(k, r, N, Tc, block_n);
+        else kblock_summary_kernel<64><<<grid, 256, 0, s>>>(k, r, N, Tc, block_n);
+    } else {
+        if (d == 128) kblock_summary_alt_kernel<128><<<grid, 256, 0, s>>>(k, r, N, Tc, block_n, repr_mode);
+        else kblock_summary_alt_kernel<64><<<grid, 256, 0, s>>>(k, r, N, Tc, block_n, repr_mode);
+    }
     return hipGetLastError() == hipSuccess ? VFA_OK : VFA_ERR_HIP;
 }
 
 int vfa_vsa_common(int mode, const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv,
                    int N, int d, int block_m, int block_n, int causal, int n_sink, int n_local, int use_minit,
                    float softmax_scale, float thr_nats, unsigned char* skip_mask, void* workspace,
-                   size_t workspace_bytes, void* stream) {
+                   size_t workspace_bytes, void* stream, int repr_mode = 0, int reorder = 1, int freeze = 1) {
     int rc = check_common(Q, K, V, O, LSE, B, Hq, Hkv, N, d, block_m, block_n);
     if (rc != VFA_OK) return rc;
     if (n_sink < 0 || n_local < 0) return VFA_ERR_INVALID_ARG;
-    if (!use_minit && n_sink + n_local == 0) return VFA_ERR_INVALID_ARG;
+    if (!use_minit && n_sink + n_local == 0 && freeze) return VFA_ERR_INVALID_ARG;
+    if (repr_mode < 0 || repr_mode > 3) return VFA_ERR_INVALID_ARG;
     if (mode == MODE_VSA && !(thr_nats > 0.f && isfinite(thr_nats))) return VFA_ERR_INVALID_ARG;
     if (!isfinite(softmax_scale)) return VFA_ERR_INVALID_ARG;
     if (use_minit < 0 || use_minit > 2) return VFA_ERR_INVALID_ARG;
@@ -1037,7 +1100,7 @@ int vfa_vsa_common(int mode, const void* Q, const void* K, const void* V, void* 
     }
     hipStream_t s = (hipStream_t)stream;
     if (use_minit == 1) {
-        rc = summary_launch(K, workspace, B, Hkv, N, d, block_n, s);
+        rc = summary_launch(K, workspace, B, Hkv, N, d, block_n, repr_mode, s);
         if (rc != VFA_OK) return rc;
     }
     Params p{};
@@ -1045,6 +1108,7 @@ int vfa_vsa_common(int mode, const void* Q, const void* K, const void* V, void* 
     p.Krepr = (const uint16_t*)workspace; p.O = (uint16_t*)O; p.LSE = LSE; p.mask = skip_mask;
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N; p.Tr = ceil_div(N, block_m); p.Tc = ceil_div(N, block_n);
     p.causal = causal ? 1 : 0; p.n_sink = n_sink; p.n_local = n_local; p.use_minit = use_minit ? 1 : 0;
+    p.order_asc = reorder ? 0 : 1; p.all_special = freeze ? 0 : 1;
     const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)d);
     p.c = scale * kLog2e;
     p.thr2 = thr_nats * kLog2e;
@@ -1080,12 +1144,18 @@ size_t vfa_workspace_bytes(int B, int Hkv, int N, int d, int block_n) {
 }
 
 int vfa_kblock_summary(const void* K, void* Krepr, int B, int Hkv, int N, int d, int block_n, void* stream) {
+    return vfa_kblock_summary_mode(K, Krepr, B, Hkv, N, d, block_n, 0, stream);
+}
+
+int vfa_kblock_summary_mode(const void* K, void* Krepr, int B, int Hkv, int N, int d, int block_n, int repr_mode,
+                            void* stream) {
     if (B < 0 || N < 0 || Hkv <= 0 || block_n <= 0) return VFA_ERR_INVALID_ARG;
+    if (repr_mode < 0 || repr_mode > 3) return VFA_ERR_INVALID_ARG;
     if (d != 64 && d != 128) return VFA_ERR_UNSUPPORTED;
     if (B == 0 || N == 0) return VFA_OK;
     if (!K || !Krepr || !aligned16(K) || !aligned16(Krepr)) return VFA_ERR_INVALID_ARG;
     if ((long long)B * Hkv > 65535) return VFA_ERR_UNSUPPORTED;
-    return summary_launch(K, Krepr, B, Hkv, N, d, block_n, (hipStream_t)stream);
+    return summary_launch(K, Krepr, B, Hkv, N, d, block_n, repr_mode, (hipStream_t)stream);
 }
 
 int fa_baseline_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int N,
@@ -1114,6 +1184,16 @@ int vsa_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LS
                  size_t workspace_bytes, void* stream) {
     return vfa_vsa_common(MODE_VSA, Q, K, V, O, LSE, B, Hq, Hkv, N, d, block_m, block_n, causal, n_sink, n_local,
                           use_minit, softmax_scale, skip_threshold_nats, skip_mask, workspace, workspace_bytes, stream);
+}
+
+int vfa_variant_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int N,
+                    int d, int block_m, int block_n, int causal, int n_sink, int n_local, int use_minit, int repr_mode,
+                    int reorder, int freeze, float softmax_scale, float skip_threshold_nats, unsigned char* skip_mask,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+    const bool skipping = skip_threshold_nats != 0.f;
+    return vfa_vsa_common(skipping ? MODE_VSA : MODE_VFA, Q, K, V, O, LSE, B, Hq, Hkv, N, d, block_m, block_n, causal,
+                          n_sink, n_local, use_minit, softmax_scale, skip_threshold_nats, skipping ? skip_mask : nullptr,
+                          workspace, workspace_bytes, stream, repr_mode, reorder, freeze);
 }
 
 const char* vfa_strerror(int code) {

@@ -69,6 +69,13 @@ def test_bad_arguments_are_rejected_before_launch(pkg):
     assert vs(*base, 1, 1, 1, 0.0, 0.0, none, p, 1 << 20, none) == -1             # threshold must be > 0
     assert vs(*base, 1, 1, 1, 0.0, float("nan"), none, p, 1 << 20, none) == -1
     assert vs(*base, 1, 1, 1, 0.0, float("inf"), none, p, 1 << 20, none) == -1
+    va = lambda *a: L.vfa_variant_fwd(*a)
+    assert va(*base, 1, 1, 1, 4, 1, 1, 0.0, 0.0, none, p, 1 << 20, none) == -1      # repr_mode out of range
+    assert va(*base, 0, 0, 0, 0, 1, 1, 0.0, 0.0, none, p, 1 << 20, none) == -1      # frozen max would stay -inf
+    assert va(*base, 1, 1, 1, 0, 0, 0, 0.0, -1.0, none, p, 1 << 20, none) == -1     # negative threshold
+    assert va(none, p, p, p, none, *ok_shape, 1, 1, 1, 0, 0, 0, 0.0, 0.0, none, p, 1 << 20, none) == -1
+    assert L.vfa_kblock_summary_mode(p, p, 1, 1, 64, 128, 64, 7, none) == -1
+    assert L.vfa_kblock_summary_mode(none, p, 1, 1, 64, 128, 64, 2, none) == -1
     assert L.vfa_kblock_summary(none, p, 1, 1, 64, 128, 64, none) == -1
     assert L.vfa_kblock_summary(p, p, 1, 1, 64, 100, 64, none) == -2
     assert L.vfa_kblock_summary(p, p, 0, 1, 64, 128, 64, none) == 0

@@ -1,0 +1,114 @@
+"""GPU parity of the ablation / variant switches (vfa_variant_fwd, vfa_kblock_summary_mode) against
+the float64 oracle run with the same switches.  Bars as in test_gpu_parity.py."""
+import numpy as np
+import pytest
+
+from paper_2604_12798_amd import workloads as wl
+
+from gpu_util import MASK_GUARD_NATS, check_o_lse, gpu_inputs, host_f32, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def vfa():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2604_12798_amd as pkg
+    pkg.lib()
+    return pkg
+
+
+def W(base="cfg2", **kw):
+    return wl.small(wl.CONFIGS[base], **kw)
+
+
+SHAPES = [
+    ("gqa_causal", W(B=2, Hq=4, Hkv=2, N=1024)),
+    ("noncausal", W(B=1, Hq=2, Hkv=2, N=768, causal=False)),
+    ("ragged_d64", W(B=1, Hq=2, Hkv=1, N=1000, d=64, F=4, block_m=64)),
+]
+
+
+@pytest.mark.parametrize("name,w", SHAPES, ids=[s[0] for s in SHAPES])
+@pytest.mark.parametrize("mode", [1, 2, 3])
+def test_ablated_block_representations(vfa, oracle, name, w, mode):
+    import torch
+    t = wl.generate(w)
+    R = vfa.kblock_summary(to_gpu(t["K"]), w.block_n, repr_mode=mode)
+    torch.cuda.synchronize()
+    got = R.float().cpu().numpy().astype(np.float64)
+    want = oracle.sabsmax(wl.bf16_bits_to_f32(t["K"]), w.block_n, mode)
+    if mode == 2:   # a mean is not an element of K: fp32 sum, one rounding to bf16
+        assert np.abs(got - want).max() <= 2.0 ** -8 * np.abs(want).max() + 1e-6
+        assert np.abs(got - want).mean() <= 2.0 ** -9 * np.abs(want).mean() + 1e-6
+    else:
+        assert np.array_equal(got, want)
+
+
+# (repr_mode, reorder, freeze, use_minit)
+SWITCHES = [(1, True, True, True), (2, True, True, True), (3, True, True, True), (0, False, True, True),
+            (0, False, True, False), (0, True, False, True), (0, False, False, False)]
+
+
+@pytest.mark.parametrize("name,w", SHAPES, ids=[s[0] for s in SHAPES])
+def test_variants_without_skipping_are_exact_attention(vfa, oracle, name, w):
+    import torch
+    t = wl.generate(w)
+    Q, K, V = gpu_inputs(t)
+    Qh, Kh, Vh = host_f32(t)
+    blocks = wl.all_blocks(w)
+    Oe, Le, Me = oracle.exact(Qh, Kh, Vh, w.block_m, w.causal, blocks)
+    for mode, reorder, freeze, minit in SWITCHES:
+        O, L, M = vfa.vfa_variant_fwd(Q, K, V, block_m=w.block_m, block_n=w.block_n, causal=w.causal, n_sink=w.n_sink,
+                                      n_local=w.n_local, use_minit=minit, repr_mode=mode, reorder=reorder, freeze=freeze)
+        torch.cuda.synchronize()
+        assert M is None
+        ref = oracle.blocks(Qh, Kh, Vh, w.block_m, w.block_n, w.causal, blocks, n_sink=w.n_sink, n_local=w.n_local,
+                            use_minit=minit, reorder=reorder, freeze=freeze,
+                            krepr=oracle.sabsmax(Kh, w.block_n, mode) if minit else None)
+        tag = "variant repr=%d reorder=%d freeze=%d minit=%d" % (mode, reorder, freeze, minit)
+        stats = check_o_lse(O, L, ref["O"], ref["LSE"], blocks, w.block_m, w.N, tag + " vs oracle")
+        check_o_lse(O, L, Oe, Le, blocks, w.block_m, w.N, tag + " vs exact")
+        gap = (Me - ref["m_final"])[~np.isnan(Me)]
+        print(name, tag, stats, "true max minus final max (nats): max %.2f" % gap.max(), flush=True)
+
+
+SKIP_CASES = [
+    ("blasst", dict(use_minit=False, reorder=False, freeze=False)),          # vanilla BLASST
+    ("blasst_swa", dict(use_minit=False, reorder=True, freeze=False)),       # BLASST in sink, local, rest order
+    ("vsa_no_reorder", dict(use_minit=True, reorder=False, freeze=True)),    # Alg. 2 without the reordering
+    ("vsa_kmax", dict(use_minit=True, reorder=True, freeze=True, repr_mode=1)),
+]
+SKIP_SHAPES = [
+    ("causal_thr4", W(B=1, Hq=4, Hkv=2, N=2048, beta=6.0, kappa=3.0), 4.0),
+    ("noncausal_thr5", W(B=1, Hq=2, Hkv=2, N=1024, beta=6.0, kappa=3.0, causal=False), 5.0),
+]
+
+
+@pytest.mark.parametrize("sname,w,thr", SKIP_SHAPES, ids=[s[0] for s in SKIP_SHAPES])
+@pytest.mark.parametrize("vname,sw", SKIP_CASES, ids=[c[0] for c in SKIP_CASES])
+def test_skipping_variants_mask_bit_exact(vfa, oracle, sname, w, thr, vname, sw):
+    import torch
+    t = wl.generate(w)
+    Q, K, V = gpu_inputs(t)
+    Qh, Kh, Vh = host_f32(t)
+    blocks = wl.all_blocks(w)
+    mode = sw.get("repr_mode", 0)
+    O, L, M = vfa.vfa_variant_fwd(Q, K, V, block_m=w.block_m, block_n=w.block_n, causal=w.causal, n_sink=w.n_sink,
+                                  n_local=w.n_local, skip_threshold_nats=thr, **sw)
+    torch.cuda.synchronize()
+    ref = oracle.blocks(Qh, Kh, Vh, w.block_m, w.block_n, w.causal, blocks, n_sink=w.n_sink, n_local=w.n_local,
+                        use_minit=sw["use_minit"], reorder=sw["reorder"], freeze=sw["freeze"], vsa=True,
+                        skip_threshold_nats=thr, krepr=oracle.sabsmax(Kh, w.block_n, mode) if sw["use_minit"] else None)
+    got = M.cpu().numpy().reshape(len(blocks), w.Tc)
+    near = np.abs(ref["margin"]) < MASK_GUARD_NATS
+    cmp = ~near
+    assert near.sum() <= 2, "too many tiles on the threshold: pick another seed"
+    assert np.array_equal(got[cmp], ref["mask"][cmp]), (vname, int((got[cmp] != ref["mask"][cmp]).sum()))
+    sparsity = (ref["mask"] == 1).sum() / max(1, (ref["mask"] != 2).sum())
+    if near.sum() == 0:
+        stats = check_o_lse(O, L, ref["O"], ref["LSE"], blocks, w.block_m, w.N, vname + " vs oracle")
+    else:
+        stats = "output not compared: %d tile(s) within the guard band" % near.sum()
+    print(sname, vname, "sparsity %.3f" % sparsity, stats, flush=True)
