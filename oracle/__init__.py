@@ -165,6 +165,25 @@ def fa_lazy(Q, K, V, block_m, block_n, causal, blocks_, tau, scale=None):
     return dict(O=O, LSE=L, counters=cnt)
 
 
+def decode(q, K, V, n_keys, block_n, *, n_sink=1, n_local=1, use_minit=True, n_parts=1, scale=None):
+    """One query token per head against the first n_keys rows of a K/V cache [B,Hkv,n_cap,d].
+    Returns dict O [B,Hq,d], LSE, m_init, m_final [B,Hq], l_parts [B,Hq,n_parts]."""
+    q = np.ascontiguousarray(q, dtype=np.float32)
+    K, V = _f32(K), _f32(V)
+    B, Hq, d = q.shape
+    Hkv, n_cap = K.shape[1], K.shape[2]
+    scale = 1.0 / math.sqrt(d) if scale is None else scale
+    krepr = np.ascontiguousarray(sabsmax(K[:, :, :n_keys], block_n), dtype=np.float64) if use_minit else None
+    O = np.full((B, Hq, d), np.nan); L = np.full((B, Hq), np.nan)
+    mi = np.full((B, Hq), np.nan); mf = np.full((B, Hq), np.nan); lp = np.full((B, Hq, n_parts), np.nan)
+    rc = _load().oracle_decode(
+        _p(q, ctypes.c_float), _p(K, ctypes.c_float), _p(V, ctypes.c_float), B, Hq, Hkv, n_cap, int(n_keys), d,
+        block_n, ctypes.c_double(scale), n_sink, n_local, _p(krepr, ctypes.c_double), n_parts, _p(O, ctypes.c_double),
+        _p(L, ctypes.c_double), _p(mi, ctypes.c_double), _p(mf, ctypes.c_double), _p(lp, ctypes.c_double))
+    assert rc == 0
+    return dict(O=O, LSE=L, m_init=mi, m_final=mf, l_parts=lp)
+
+
 def fa2(Q, K, V, block_m, block_n, causal, blocks_, scale=None, want_traj=False):
     """FA column of Table 1: ascending order, exact-max update on every block."""
     return blocks(Q, K, V, block_m, block_n, causal, blocks_, n_sink=0, n_local=0, use_minit=False,

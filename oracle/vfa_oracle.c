@@ -427,3 +427,73 @@ int oracle_fa_lazy(const float *Q, const float *K, const float *V, int B, int Hq
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------ */
+/* Decode step against a key/value cache (Step 1: summaries of a growing cache are extended block
+ * by block; the rest is Alg. 1 with a query block of one token per head that sees every key).
+ *   q [B,Hq,d]; K, V [B,Hkv,n_cap,d] of which the first n_keys rows are valid
+ *   krepr [B,Hkv,ceil(n_keys/block_n),d] or NULL (then m_init = -inf)
+ *   O [B,Hq,d], LSE [B,Hq]: the plain definition over keys 0..n_keys-1, two passes
+ *   m_init [B,Hq]: max_j scale * q . krepr_j over all blocks of the cache
+ *   m_final [B,Hq]: max(m_init, exact max over the keys of the first n_sink blocks and of the
+ *     last n_local blocks): the value Alg. 1's max holds once its sink / local blocks are done,
+ *     and the one a split of the remaining blocks over several workers can share.
+ * Because every later block is accumulated against m_final with no further update, the partial
+ * (sum exp(s - m_final) v, sum exp(s - m_final)) of disjoint key ranges ADD: l_parts [B,Hq,n_parts]
+ * returns the second of these for n_parts equal ranges of whole blocks so that a test can check
+ * that they sum to exp(LSE - m_final).                                                     */
+int oracle_decode(const float *q, const float *K, const float *V, int B, int Hq, int Hkv, int n_cap,
+                  int n_keys, int d, int block_n, double scale, int n_sink, int n_local,
+                  const double *krepr, int n_parts, double *O, double *LSE, double *m_init,
+                  double *m_final, double *l_parts) {
+    if (Hq % Hkv != 0 || n_keys < 1 || n_keys > n_cap || block_n <= 0 || n_parts < 1) return -1;
+    const int g = Hq / Hkv, Tc = ceil_div(n_keys, block_n);
+    const int per = ceil_div(Tc, n_parts);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int bh = 0; bh < B * Hq; ++bh) {
+        const int b = bh / Hq, h = bh % Hq, hkv = h / g;
+        const float *qr = q + (size_t)bh * d;
+        const float *Kh = K + ((size_t)b * Hkv + hkv) * n_cap * d;
+        const float *Vh = V + ((size_t)b * Hkv + hkv) * n_cap * d;
+        double *s = (double *)malloc((size_t)n_keys * sizeof(double));
+        double mx = -INFINITY, sum = 0.0;
+        for (int c = 0; c < n_keys; ++c) {
+            double a = 0.0;
+            for (int t = 0; t < d; ++t) a += (double)qr[t] * (double)Kh[(size_t)c * d + t];
+            s[c] = scale * a;
+            mx = fmax(mx, s[c]);
+        }
+        double mi = -INFINITY;
+        if (krepr)
+            for (int j = 0; j < Tc; ++j) {
+                const double *kr = krepr + (((size_t)b * Hkv + hkv) * Tc + j) * d;
+                double a = 0.0;
+                for (int t = 0; t < d; ++t) a += (double)qr[t] * kr[t];
+                mi = fmax(mi, scale * a);
+            }
+        double mf = mi;
+        for (int j = 0; j < Tc; ++j)
+            if (j < n_sink || j >= Tc - n_local)
+                for (int c = j * block_n; c < imin(n_keys, (j + 1) * block_n); ++c) mf = fmax(mf, s[c]);
+        if (l_parts)
+            for (int part = 0; part < n_parts; ++part) {
+                double lp = 0.0;
+                for (int c = part * per * block_n; c < imin(n_keys, (part + 1) * per * block_n); ++c)
+                    lp += exp(s[c] - mf);
+                l_parts[(size_t)bh * n_parts + part] = lp;
+            }
+        double *o = O + (size_t)bh * d;
+        for (int t = 0; t < d; ++t) o[t] = 0.0;
+        for (int c = 0; c < n_keys; ++c) {
+            const double pc = exp(s[c] - mx);
+            sum += pc;
+            for (int t = 0; t < d; ++t) o[t] += pc * (double)Vh[(size_t)c * d + t];
+        }
+        for (int t = 0; t < d; ++t) o[t] /= sum;
+        LSE[bh] = mx + log(sum);
+        if (m_init) m_init[bh] = mi;
+        if (m_final) m_final[bh] = mf;
+        free(s);
+    }
+    return 0;
+}

@@ -333,6 +333,42 @@ def test_lazy_rescale_is_exact_and_runs_the_rescale_less_often(oracle):
             assert got[n] == changed
 
 
+def test_decode_step_is_last_row_of_causal_prefill_and_parts_add(oracle):
+    """A decode step over n keys is the last row of causal attention over n tokens (library softmax
+    here, and the pinned prefill oracle); with the max fixed after the sink / local blocks the
+    per-range sums of exp(s - m) simply add up (Step 3: no rescale, hence no max in the merge)."""
+    B, Hq, Hkv, n_cap, d, bn = 2, 4, 2, 200, 8, 16
+    K, V = rnd(50, B, Hkv, n_cap, d), rnd(51, B, Hkv, n_cap, d)
+    Qfull = 2.0 * rnd(52, B, Hq, n_cap, d)
+    for n_keys in (1, 16, 17, 150, 200):
+        q = np.ascontiguousarray(Qfull[:, :, n_keys - 1])
+        out = oracle.decode(q, K, V, n_keys, bn, n_sink=1, n_local=2, n_parts=3)
+        for b in range(B):
+            for h in range(Hq):
+                s = (K[b, h // 2, :n_keys].astype(np.float64) @ q[b, h].astype(np.float64)) / math.sqrt(d)
+                p = scipy.special.softmax(s)
+                assert np.abs(out["O"][b, h] - p @ V[b, h // 2, :n_keys].astype(np.float64)).max() < 1e-12
+                assert abs(out["LSE"][b, h] - scipy.special.logsumexp(s)) < 1e-12
+                Tc = -(-n_keys // bn)
+                special = [c for c in range(n_keys) if c // bn < 1 or c // bn >= Tc - 2]
+                assert out["m_final"][b, h] >= out["m_init"][b, h]
+                assert abs(out["m_final"][b, h] - max(out["m_init"][b, h], s[special].max())) < 1e-12
+                assert abs(out["l_parts"][b, h].sum() - math.exp(out["LSE"][b, h] - out["m_final"][b, h])) < 1e-9 * out["l_parts"][b, h].sum()
+        if n_keys == n_cap:   # the prefill oracle's last causal row
+            blocks = np.array([(b, h, (n_keys - 1) // 8) for b in range(B) for h in range(Hq)], np.int32)
+            Oe, Le, _ = oracle.exact(Qfull, K, V, 8, True, blocks)
+            assert np.abs(Oe[:, (n_keys - 1) % 8].reshape(B, Hq, d) - out["O"]).max() < 1e-12
+    # m_init is the max of q . summary over the cache's blocks (sabsmax pinned elsewhere)
+    n_keys = 150
+    q = np.ascontiguousarray(Qfull[:, :, 0])
+    out = oracle.decode(q, K, V, n_keys, bn)
+    R = oracle.sabsmax(K[:, :, :n_keys], bn)
+    for b in range(B):
+        for h in range(Hq):
+            assert abs(out["m_init"][b, h] - (R[b, h // 2] @ q[b, h].astype(np.float64)).max() / math.sqrt(d)) < 1e-12
+    assert np.isneginf(oracle.decode(q, K, V, n_keys, bn, use_minit=False, n_sink=0, n_local=0)["m_final"]).all()
+
+
 # ------------------------------------------------------------------ VSA
 def _vsa_problem(seed=30, N=256, d=8, causal=True):
     w = wl.small(wl.CONFIGS["cfg2"], B=1, Hq=2, Hkv=1, N=N, d=d, block_m=32, block_n=16, F=1, W=16.0, theta=4.0,
