@@ -73,6 +73,31 @@ def cpu_baseline(w: wl.Workload, t: dict, n_random: int):
                       f"{w.dense_flop() / (flop / dt):.0f} s"}
 
 
+def decode_step(args, torch, vfa):
+    """One decode step (summaries of the cache kept up to date beforehand) on the decode workload: HBM bound,
+    algorithmic bytes = the K and V cache rows read once."""
+    w, ns = wl.DECODE, wl.DECODE_SPLITS
+    n_keys = w.N
+    t = wl.generate_decode(w, n_keys, args.seed)
+    dev = torch.device("cuda:0")
+    q, K, V = (torch.from_numpy(t[k].view(np.int16)).to(dev).view(torch.bfloat16) for k in ("q", "K", "V"))
+    R = torch.empty((w.B, w.Hkv, w.Tc, w.d), dtype=torch.bfloat16, device=dev)
+    vfa.kblock_summary_append(K, R, 0, n_keys, w.block_n)
+    O = torch.empty_like(q)
+    L = torch.empty((w.B, w.Hq), dtype=torch.float32, device=dev)
+    ws = torch.empty(vfa.decode_workspace_bytes(w.B, w.Hq, w.d, ns), dtype=torch.uint8, device=dev)
+
+    def run():
+        vfa.decode_fwd(q, K, V, n_keys, krepr=R, block_n=w.block_n, n_sink=w.n_sink, n_local=w.n_local, n_splits=ns,
+                       workspace=ws, out=O, lse=L)
+
+    ms = time_region(run, max(args.steps, 20), args.warmup)
+    nbytes = 2.0 * w.B * w.Hkv * n_keys * w.d * 2
+    return {"workload": f"{w.name}: B={w.B} Hq={w.Hq} Hkv={w.Hkv} cached keys={n_keys} d={w.d}, {ns} key splits",
+            "us_per_step": ms * 1e3, "bound": "hbm", "bytes": nbytes, "achieved_GB/s": nbytes / ms / 1e6,
+            "peak_GB/s": 8000.0, "frac": nbytes / ms / 1e6 / 8000.0}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -82,7 +107,7 @@ def main():
     ap.add_argument("--seed", type=int, default=wl.DEFAULT_SEED)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=1500, help="random query blocks in the oracle timing sample")
-    ap.add_argument("--only", default="", help="comma list of fa,vfa,vsa,summary to time (default all)")
+    ap.add_argument("--only", default="", help="comma list of fa,vfa,vsa,summary,decode to time (default all)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is a single-GPU kernel path; run it with --gpus 1 "
@@ -102,7 +127,7 @@ def main():
     M = torch.empty((w.B, w.Hq, w.Tr, w.Tc), dtype=torch.uint8, device=dev)
     kw = dict(block_m=w.block_m, block_n=w.block_n, causal=w.causal, out=O, lse=L)
     vkw = dict(n_sink=w.n_sink, n_local=w.n_local, workspace=ws, **kw)
-    only = set(filter(None, args.only.split(","))) or {"fa", "vfa", "vsa", "summary"}
+    only = set(filter(None, args.only.split(","))) or {"fa", "vfa", "vsa", "summary", "decode"}
 
     def run_vfa():
         vfa.vfa_attn_fwd(Q, K, V, use_minit=1, **vkw)
@@ -165,6 +190,8 @@ def main():
                       "algorithmic_tflops": dense * (2.0 - sparsity) / 2.0 / ms_vsa / 1e9,
                       "speedup_vs_fa": (out["baseline_fa"]["ms_per_step"] / ms_vsa) if "fa" in only else None,
                       "speedup_vs_vfa": ms_vfa / ms_vsa}
+    if "decode" in only:
+        out["decode"] = decode_step(args, torch, vfa)
     out["paper_context"] = ("paper reports no measured kernel throughput; its analytic model gives ~2x for C8V32/C4V32/C4V16 "
                             "over C16V32 and 1.00x for VFA vs FA at C16V32 (the bf16 analogue) on its own accelerator")
     if not args.no_cpu_baseline:

@@ -122,6 +122,38 @@ int vfa_variant_fwd(const void* Q, const void* K, const void* V, void* O, float*
                     float softmax_scale, float skip_threshold_nats, unsigned char* skip_mask,
                     void* workspace, size_t workspace_bytes, void* stream);
 
+/* Summaries of a growing key cache (Methods, Step 1: "for decoding with a growing KV-cache, this
+ * precomputation can be performed incrementally for newly appended key blocks").  K is a cache
+ * [B, Hkv, n_cap, d] whose first n_new rows are valid, of which rows [n_old, n_new) are new;
+ * Krepr is [B, Hkv, ceil(n_cap / block_n), d] (vfa_workspace_bytes(B, Hkv, n_cap, d, block_n)
+ * bytes).  Recomputes exactly the summaries of the blocks that contain new rows (a partly filled
+ * last block is summarised over its valid rows); all others are left as they are.
+ * VFA_ERR_INVALID_ARG unless 0 <= n_old <= n_new <= n_cap. */
+int vfa_kblock_summary_append(const void* K, void* Krepr, int B, int Hkv, int n_cap, int n_old,
+                              int n_new, int d, int block_n, void* stream);
+
+/* Bytes of workspace vfa_decode_fwd needs (partial sums of n_splits key ranges per query head). */
+size_t vfa_decode_workspace_bytes(int B, int Hq, int d, int n_splits);
+
+/* Decode step (Alg. 1 with one query token per head that sees every cached key; the split over
+ * key ranges uses Step 3: once the max is frozen, partial sums need no rescale).
+ *   Q [B, Hq, d], O [B, Hq, d] bf16; LSE [B, Hq] fp32 or NULL
+ *   K, V [B, Hkv, n_cap, d] bf16, rows [0, n_keys) valid (rows beyond are never read)
+ *   Krepr  summaries of those n_keys rows, laid out for n_cap (see vfa_kblock_summary_append);
+ *          read when use_minit == 1, may be NULL when use_minit == 0
+ * The running max is m = max(m_init, exact row max over the first n_sink and the last n_local key
+ * blocks), m_init = max_j scale * q . Krepr_j (or -inf); the cache is cut into n_splits ranges of
+ * whole blocks; each range accumulates sum exp(s - m) and sum exp(s - m) v; the ranges are added in
+ * index order (bit-identical results from run to run), divided, and LSE = m + ln l.  The result is
+ * exact attention over the n_keys rows.  n_splits >= 1 (ranges may be empty); Hq / Hkv <= 32;
+ * block_n = 64; d in {64, 128}.  workspace: vfa_decode_workspace_bytes(...) bytes, 16-byte aligned,
+ * contents irrelevant on entry.  VFA_ERR_INVALID_ARG for n_keys < 1 or > n_cap, for
+ * use_minit == 0 with n_sink + n_local == 0, and for the pointer / size errors listed above. */
+int vfa_decode_fwd(const void* Q, const void* K, const void* V, const void* Krepr, void* O,
+                   float* LSE, int B, int Hq, int Hkv, int n_cap, int n_keys, int d, int block_n,
+                   int n_sink, int n_local, int use_minit, int n_splits, float softmax_scale,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
 /* Static string for a return code. */
 const char* vfa_strerror(int code);
 

@@ -14,7 +14,8 @@ LIB_PATH = os.path.join(_HERE, "libvfa.so")
 _lib = None
 
 EXPORTS = ("vfa_workspace_bytes", "vfa_kblock_summary", "vfa_kblock_summary_mode", "fa_baseline_fwd",
-           "fa_lazy_rescale_fwd", "vfa_attn_fwd", "vsa_attn_fwd", "vfa_variant_fwd", "vfa_strerror")
+           "fa_lazy_rescale_fwd", "vfa_attn_fwd", "vsa_attn_fwd", "vfa_variant_fwd", "vfa_kblock_summary_append",
+           "vfa_decode_workspace_bytes", "vfa_decode_fwd", "vfa_strerror")
 
 
 class VfaError(RuntimeError):
@@ -39,6 +40,12 @@ def lib() -> ctypes.CDLL:
         L.vfa_kblock_summary_mode.argtypes = [vp, vp, i, i, i, i, i, i, vp]
         L.vfa_variant_fwd.restype = i
         L.vfa_variant_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, i, i, i, i, i, f, f, vp, vp, sz, vp]
+        L.vfa_kblock_summary_append.restype = i
+        L.vfa_kblock_summary_append.argtypes = [vp, vp, i, i, i, i, i, i, i, vp]
+        L.vfa_decode_workspace_bytes.restype = sz
+        L.vfa_decode_workspace_bytes.argtypes = [i, i, i, i]
+        L.vfa_decode_fwd.restype = i
+        L.vfa_decode_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, i, i, f, vp, sz, vp]
         L.fa_baseline_fwd.restype = i
         L.fa_baseline_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, f, vp]
         L.fa_lazy_rescale_fwd.restype = i
@@ -188,3 +195,38 @@ def vfa_variant_fwd(Q, K, V, *, block_m=128, block_n=64, causal=True, n_sink=1, 
     if rc != 0:
         raise VfaError(rc, "vfa_variant_fwd")
     return O, L, M
+
+
+def kblock_summary_append(K, Krepr, n_old: int, n_new: int, block_n: int = 64, stream=None):
+    """Refresh, in place, the summaries of the blocks of cache K [B, Hkv, n_cap, d] that hold rows [n_old, n_new)."""
+    B, Hkv, n_cap, d = K.shape
+    rc = lib().vfa_kblock_summary_append(_ptr(K), _ptr(Krepr), B, Hkv, n_cap, int(n_old), int(n_new), d, block_n,
+                                         _stream(stream))
+    if rc != 0:
+        raise VfaError(rc, "vfa_kblock_summary_append")
+    return Krepr
+
+
+def decode_workspace_bytes(B: int, Hq: int, d: int, n_splits: int) -> int:
+    return int(lib().vfa_decode_workspace_bytes(B, Hq, d, n_splits))
+
+
+def decode_fwd(q, K, V, n_keys: int, *, krepr=None, block_n=64, n_sink=1, n_local=1, use_minit=True, n_splits=8,
+               softmax_scale=0.0, workspace=None, out=None, lse=None, want_lse=True, stream=None):
+    """One query token per head, q [B, Hq, d], against the first n_keys rows of the cache K, V [B, Hkv, n_cap, d]."""
+    import torch
+    B, Hq, d = q.shape
+    Hkv, n_cap = K.shape[1], K.shape[2]
+    for t in (q, K, V):
+        if not (t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()):
+            raise ValueError("q, K, V must be contiguous bf16 tensors on the GPU")
+    O = torch.empty_like(q) if out is None else out
+    L = lse if (lse is not None or not want_lse) else torch.empty((B, Hq), dtype=torch.float32, device=q.device)
+    need = decode_workspace_bytes(B, Hq, d, n_splits)
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device) if workspace is None else workspace
+    rc = lib().vfa_decode_fwd(_ptr(q), _ptr(K), _ptr(V), _ptr(krepr), _ptr(O), _ptr(L), B, Hq, Hkv, n_cap, int(n_keys), d,
+                              block_n, int(n_sink), int(n_local), int(bool(use_minit)), int(n_splits), float(softmax_scale),
+                              _ptr(ws), ws.numel() * ws.element_size(), _stream(stream))
+    if rc != 0:
+        raise VfaError(rc, "vfa_decode_fwd")
+    return O, L

@@ -25,6 +25,7 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
@@ -946,15 +947,18 @@ __device__ inline uint32_t sabs_pick2(uint32_t a, uint32_t b) {  // two packed b
     return sabs_pick(a & 0xffffu, b & 0xffffu) | (sabs_pick(a >> 16, b >> 16) << 16);
 }
 
+// N = row stride of one head's key array (its capacity), n_valid = keys present, Tc = block stride of
+// one head's summary array, j0 = first block to (re)compute: a growing cache recomputes only the
+// blocks that received keys.
 template <int D>
 __global__ __launch_bounds__(256) void kblock_summary_kernel(const uint16_t* __restrict__ K, uint16_t* __restrict__ R,
-                                                             int N, int Tc, int block_n) {
+                                                             int N, int n_valid, int Tc, int block_n, int j0) {
     constexpr int CH = D / 8;        // 16-byte chunks per row
     constexpr int RG = 256 / CH;     // row groups
     __shared__ u32x4 part[RG][CH];
-    const int j = blockIdx.x, bh = blockIdx.y;
+    const int j = j0 + blockIdx.x, bh = blockIdx.y;
     const int ch = threadIdx.x % CH, rg = threadIdx.x / CH;
-    const int c0 = j * block_n, c1 = min(N, c0 + block_n);
+    const int c0 = j * block_n, c1 = min(n_valid, c0 + block_n);
     const uint16_t* base = K + (size_t)bh * N * D;
     u32x4 acc = {0, 0, 0, 0};
     for (int r = c0 + rg; r < c1; r += RG) {
@@ -1020,6 +1024,149 @@ __global__ __launch_bounds__(256) void kblock_summary_alt_kernel(const uint16_t*
 }
 
 // ---------------------------------------------------------------------------------------------
+// Decode: one query token per head against a key/value cache, the keys split over workgroups.
+// A wave carries the Hq / Hkv (<= 32) query heads of one KV head as the columns of its score tile
+// (unused columns repeat the last head).  Three small kernels:
+//   decode_max_kernel    per (KV head, split): max of q . summary over the split's share of the cache's
+//                        block summaries, and the exact max over its share of the sink / local tiles
+//   decode_split_kernel  per (KV head, split): with m = the max of all those partial maxima, fixed,
+//                        sum exp(s - m) and sum exp(s - m) v over the split's key range
+//   decode_merge_kernel  per query head: ADD the partial sums (no max in the merge, because no split
+//                        ever rescales), divide, write O and LSE
+// The work is HBM bound (K and V are read once), so single-wave workgroups with a two-deep tile ring
+// (64 KiB of LDS, two per CU) and the same tile helpers as the prefill kernels are enough.
+struct DecodeParams {
+    const uint16_t* Q;      // [B, Hq, d]
+    const uint16_t* K;      // [B, Hkv, n_cap, d]
+    const uint16_t* V;
+    const uint16_t* Krepr;  // [B, Hkv, tc_cap, d]
+    float* pm;              // [B * Hq, n_splits]     partial maxima, log2 units
+    float* lpart;           // [B * Hq, n_splits]     partial sums of exp
+    float* opart;           // [B * Hq, n_splits, d]  partial sums of exp * v
+    uint16_t* O;            // [B, Hq, d]
+    float* LSE;             // [B, Hq] or null
+    int B, Hq, Hkv, n_cap, n_keys, tc_cap, n_splits, n_sink, n_local, use_minit;
+    float c;
+};
+
+template <int D>
+__device__ __forceinline__ void decode_rows(const DecodeParams& p, int bh, int lane, int& b, int& h, bf16x8* qf) {
+    const int g = p.Hq / p.Hkv, hkv = bh % p.Hkv;
+    b = bh / p.Hkv;
+    h = hkv * g + min(lane & 31, g - 1);
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk)
+        qf[kk] = *reinterpret_cast<const bf16x8*>(p.Q + ((size_t)b * p.Hq + h) * D + 16 * kk + 8 * (lane >> 5));
+}
+
+template <int D>
+__global__ __launch_bounds__(64) void decode_max_kernel(const DecodeParams p) {
+    using T = Tile<D>;
+    __shared__ __attribute__((aligned(16))) uint8_t buf[T::BYTES];
+    const int lane = threadIdx.x, ql = lane & 31, hh = lane >> 5;
+    const int split = blockIdx.x, bh = blockIdx.y;
+    int b, h;
+    bf16x8 qf[D / 16];
+    decode_rows<D>(p, bh, lane, b, h, qf);
+    const int Tc = (p.n_keys + BN - 1) / BN;
+    float mx = -INFINITY;
+    f32x16 st[2];
+    if (p.use_minit) {
+        const uint16_t* Rg = p.Krepr + (size_t)bh * p.tc_cap * D;
+        for (int ts = split; ts * BN < Tc; ts += p.n_splits) {
+            load_tile<D, 1>(Rg, ts * BN, Tc, buf, false, 0, lane);
+            wait_vm0_and_sync();
+            qk_tile_pipe<D>(buf, qf, st, ql, hh);
+            mx = fmaxf(mx, tile_rowmax<true>(st, ts * BN, Tc - 1, hh));
+            __syncthreads();
+        }
+    }
+    // sink tiles [0, n1) and local tiles [lo2, Tc): dealt round-robin over the splits
+    const int n1 = min(p.n_sink, Tc), lo2 = max(n1, Tc - p.n_local);
+    const uint16_t* Kg = p.K + (size_t)bh * p.n_cap * D;
+    for (int u = split; u < n1 + (Tc - lo2); u += p.n_splits) {
+        const int j = u < n1 ? u : lo2 + (u - n1);
+        load_tile<D, 1>(Kg, j * BN, p.n_keys, buf, false, 0, lane);
+        wait_vm0_and_sync();
+        qk_tile_pipe<D>(buf, qf, st, ql, hh);
+        mx = fmaxf(mx, tile_rowmax<true>(st, j * BN, p.n_keys - 1, hh));
+        __syncthreads();
+    }
+    const float m2 = xhalf_max(mx) * p.c;
+    if (ql < p.Hq / p.Hkv && hh == 0) p.pm[((size_t)b * p.Hq + h) * p.n_splits + split] = m2;
+}
+
+template <int D>
+__global__ __launch_bounds__(64) void decode_split_kernel(const DecodeParams p) {
+    using T = Tile<D>;
+    constexpr int DB = D / 32;
+    __shared__ __attribute__((aligned(16))) uint8_t smem[4 * T::BYTES];  // K[2], V[2]
+    uint8_t* const Ks = smem;
+    uint8_t* const Vs = smem + 2 * T::BYTES;
+    const int lane = threadIdx.x, ql = lane & 31, hh = lane >> 5;
+    const int split = blockIdx.x, bh = blockIdx.y;
+    int b, h;
+    bf16x8 qf[D / 16];
+    decode_rows<D>(p, bh, lane, b, h, qf);
+    const size_t row = (size_t)b * p.Hq + h;
+    float m2 = -INFINITY;
+    for (int s = 0; s < p.n_splits; ++s) m2 = fmaxf(m2, p.pm[row * p.n_splits + s]);
+
+    const int Tc = (p.n_keys + BN - 1) / BN;
+    const int per = (Tc + p.n_splits - 1) / p.n_splits;
+    const int t_lo = split * per, t_hi = min(Tc, t_lo + per);
+    const uint16_t* Kg = p.K + (size_t)bh * p.n_cap * D;
+    const uint16_t* Vg = p.V + (size_t)bh * p.n_cap * D;
+    f32x16 ot[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) ot[db] = f32x16{0};
+    float lsum = 0.f;
+    if (t_lo < t_hi) {
+        load_tile<D, 1>(Kg, t_lo * BN, p.n_keys, Ks, false, 0, lane);
+        load_tile<D, 1>(Vg, t_lo * BN, p.n_keys, Vs, true, 0, lane);
+        wait_vm0_and_sync();
+    }
+    for (int t = t_lo; t < t_hi; ++t) {
+        const int cur = (t - t_lo) & 1;
+        if (t + 1 < t_hi) {
+            load_tile<D, 1>(Kg, (t + 1) * BN, p.n_keys, Ks + (cur ^ 1) * T::BYTES, false, 0, lane);
+            load_tile<D, 1>(Vg, (t + 1) * BN, p.n_keys, Vs + (cur ^ 1) * T::BYTES, true, 0, lane);
+        }
+        f32x16 st[2];
+        uint32_t pk[16];
+        qk_tile_pipe<D>(Ks + cur * T::BYTES, qf, st, ql, hh);
+        softmax_tile<false, true, DB>(st, pk, ot, m2, lsum, p.c, t * BN, p.n_keys - 1, hh);  // frozen max, ragged tail masked
+        pv_tile_pipe<D>(Vs + cur * T::BYTES, pk, ot, lane, hh);
+        wait_vm0_and_sync();
+    }
+    const float l = xhalf_sum(lsum);
+    if (ql < p.Hq / p.Hkv) {
+        if (hh == 0) p.lpart[row * p.n_splits + split] = l;
+        float* og = p.opart + (row * p.n_splits + split) * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4)
+                *reinterpret_cast<f32x4*>(og + 32 * db + 8 * q4 + 4 * hh) =
+                    f32x4{ot[db][4 * q4], ot[db][4 * q4 + 1], ot[db][4 * q4 + 2], ot[db][4 * q4 + 3]};
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(D) void decode_merge_kernel(const DecodeParams p) {
+    const size_t row = blockIdx.x;
+    const int t = threadIdx.x;
+    float m2 = -INFINITY, l = 0.f, o = 0.f;
+    for (int s = 0; s < p.n_splits; ++s) {  // fixed order: the result does not depend on scheduling
+        m2 = fmaxf(m2, p.pm[row * p.n_splits + s]);
+        l += p.lpart[row * p.n_splits + s];
+        o += p.opart[(row * p.n_splits + s) * D + t];
+    }
+    p.O[row * D + t] = (uint16_t)(pack_bf16(l > 0.f ? o / l : 0.f, 0.f) & 0xffffu);
+    if (p.LSE && t == 0) p.LSE[row] = l > 0.f ? (m2 + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
+}
+
+// ---------------------------------------------------------------------------------------------
 // host side
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
@@ -1071,8 +1218,8 @@ int summary_launch(const void* K, void* Krepr, int B, int Hkv, int N, int d, int
     uint16_t* r = (uint16_t*)Krepr;
     (void)hipGetLastError();
     if (repr_mode == 0) {
-        if (d == 128) kblock_summary_kernel<128><<<grid, 256, 0, s>>>(k, r, N, Tc, block_n);
-        else kblock_summary_kernel<64><<<grid, 256, 0, s>>>(k, r, N, Tc, block_n);
+        if (d == 128) kblock_summary_kernel<128><<<grid, 256, 0, s>>>(k, r, N, N, Tc, block_n, 0);
+        else kblock_summary_kernel<64><<<grid, 256, 0, s>>>(k, r, N, N, Tc, block_n, 0);
     } else {
         if (d == 128) kblock_summary_alt_kernel<128><<<grid, 256, 0, s>>>(k, r, N, Tc, block_n, repr_mode);
         else kblock_summary_alt_kernel<64><<<grid, 256, 0, s>>>(k, r, N, Tc, block_n, repr_mode);
@@ -1194,6 +1341,74 @@ int vfa_variant_fwd(const void* Q, const void* K, const void* V, void* O, float*
     return vfa_vsa_common(skipping ? MODE_VSA : MODE_VFA, Q, K, V, O, LSE, B, Hq, Hkv, N, d, block_m, block_n, causal,
                           n_sink, n_local, use_minit, softmax_scale, skip_threshold_nats, skipping ? skip_mask : nullptr,
                           workspace, workspace_bytes, stream, repr_mode, reorder, freeze);
+}
+
+int vfa_kblock_summary_append(const void* K, void* Krepr, int B, int Hkv, int n_cap, int n_old, int n_new, int d,
+                              int block_n, void* stream) {
+    if (B < 0 || Hkv <= 0 || n_cap < 0 || block_n <= 0) return VFA_ERR_INVALID_ARG;
+    if (n_old < 0 || n_new < n_old || n_new > n_cap) return VFA_ERR_INVALID_ARG;
+    if (d != 64 && d != 128) return VFA_ERR_UNSUPPORTED;
+    if (B == 0 || n_new == n_old) return VFA_OK;
+    if (!K || !Krepr || !aligned16(K) || !aligned16(Krepr)) return VFA_ERR_INVALID_ARG;
+    if ((long long)B * Hkv > 65535) return VFA_ERR_UNSUPPORTED;
+    const int j0 = n_old / block_n, j1 = ceil_div(n_new, block_n);  // blocks [j0, j1) received keys
+    const int tc_cap = ceil_div(n_cap, block_n);
+    const dim3 grid((unsigned)(j1 - j0), (unsigned)(B * Hkv));
+    hipStream_t s = (hipStream_t)stream;
+    (void)hipGetLastError();
+    if (d == 128)
+        kblock_summary_kernel<128><<<grid, 256, 0, s>>>((const uint16_t*)K, (uint16_t*)Krepr, n_cap, n_new, tc_cap, block_n, j0);
+    else
+        kblock_summary_kernel<64><<<grid, 256, 0, s>>>((const uint16_t*)K, (uint16_t*)Krepr, n_cap, n_new, tc_cap, block_n, j0);
+    return hipGetLastError() == hipSuccess ? VFA_OK : VFA_ERR_HIP;
+}
+
+size_t vfa_decode_workspace_bytes(int B, int Hq, int d, int n_splits) {
+    if (B <= 0 || Hq <= 0 || d <= 0 || n_splits <= 0) return 0;
+    const size_t bytes = (size_t)B * Hq * n_splits * (2 + (size_t)d) * sizeof(float);
+    return (bytes + 255) & ~(size_t)255;
+}
+
+int vfa_decode_fwd(const void* Q, const void* K, const void* V, const void* Krepr, void* O, float* LSE, int B, int Hq,
+                   int Hkv, int n_cap, int n_keys, int d, int block_n, int n_sink, int n_local, int use_minit,
+                   int n_splits, float softmax_scale, void* workspace, size_t workspace_bytes, void* stream) {
+    if (B < 0 || Hq <= 0 || Hkv <= 0 || n_cap <= 0 || d <= 0 || block_n <= 0) return VFA_ERR_INVALID_ARG;
+    if (Hq % Hkv != 0 || n_sink < 0 || n_local < 0 || n_splits < 1 || n_splits > 4096) return VFA_ERR_INVALID_ARG;
+    if (n_keys < 1 || n_keys > n_cap) return VFA_ERR_INVALID_ARG;
+    if (use_minit != 0 && use_minit != 1) return VFA_ERR_INVALID_ARG;
+    if (!use_minit && n_sink + n_local == 0) return VFA_ERR_INVALID_ARG;
+    if (!isfinite(softmax_scale)) return VFA_ERR_INVALID_ARG;
+    if ((d != 64 && d != 128) || block_n != BN || Hq / Hkv > 32) return VFA_ERR_UNSUPPORTED;
+    if (B == 0) return VFA_OK;
+    if (!Q || !K || !V || !O || !workspace || (use_minit && !Krepr)) return VFA_ERR_INVALID_ARG;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(workspace) ||
+        (use_minit && !aligned16(Krepr)))
+        return VFA_ERR_INVALID_ARG;
+    if (LSE && (reinterpret_cast<uintptr_t>(LSE) & 3u)) return VFA_ERR_INVALID_ARG;
+    if (workspace_bytes < vfa_decode_workspace_bytes(B, Hq, d, n_splits)) return VFA_ERR_INVALID_ARG;
+    if ((long long)B * Hkv > 65535 || (long long)B * Hq > 0x7fffffffLL) return VFA_ERR_UNSUPPORTED;
+    DecodeParams p{};
+    p.Q = (const uint16_t*)Q; p.K = (const uint16_t*)K; p.V = (const uint16_t*)V; p.Krepr = (const uint16_t*)Krepr;
+    p.O = (uint16_t*)O; p.LSE = LSE;
+    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.n_cap = n_cap; p.n_keys = n_keys; p.tc_cap = ceil_div(n_cap, block_n);
+    p.n_splits = n_splits; p.n_sink = n_sink; p.n_local = n_local; p.use_minit = use_minit;
+    const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)d);
+    p.c = scale * kLog2e;
+    const size_t rows = (size_t)B * Hq * n_splits;
+    p.opart = (float*)workspace; p.pm = p.opart + rows * d; p.lpart = p.pm + rows;  // the 16-byte stores go first
+    hipStream_t s = (hipStream_t)stream;
+    const dim3 grid((unsigned)n_splits, (unsigned)(B * Hkv));
+    (void)hipGetLastError();
+    if (d == 128) {
+        decode_max_kernel<128><<<grid, 64, 0, s>>>(p);
+        decode_split_kernel<128><<<grid, 64, 0, s>>>(p);
+        decode_merge_kernel<128><<<(unsigned)(B * Hq), 128, 0, s>>>(p);
+    } else {
+        decode_max_kernel<64><<<grid, 64, 0, s>>>(p);
+        decode_split_kernel<64><<<grid, 64, 0, s>>>(p);
+        decode_merge_kernel<64><<<(unsigned)(B * Hq), 64, 0, s>>>(p);
+    }
+    return hipGetLastError() == hipSuccess ? VFA_OK : VFA_ERR_HIP;
 }
 
 const char* vfa_strerror(int code) {

@@ -188,6 +188,36 @@ def generate(w: Workload, seed: int = DEFAULT_SEED) -> dict:
     return {"Q": f32_to_bf16_bits(Q), "K": f32_to_bf16_bits(K), "V": f32_to_bf16_bits(V)}
 
 
+def generate_decode(w: Workload, n_keys: int, seed: int = DEFAULT_SEED) -> dict:
+    """Decode-step inputs in the "sinklocal" recipe: {"q" [B,Hq,d], "K","V" [B,Hkv,N,d]} as bf16 bits.
+    K and V are the cache (w.N = its capacity; rows >= n_keys are filled too but are never to be read),
+    q is the query of the token at position n_keys - 1 (same sink direction, same positional dims)."""
+    assert w.kind == "sinklocal" and 1 <= n_keys <= w.N
+    B, Hq, Hkv, N, d = w.B, w.Hq, w.Hkv, w.N, w.d
+    g = Hq // Hkv
+    q = _normal(seed, 6, (B, Hq, d))
+    K = _normal(seed, 2, (B, Hkv, N, d))
+    V = _normal(seed, 3, (B, Hkv, N, d))
+    nd = d - 2 * max(w.F, 0)
+    a = _normal(seed, 4, (B, Hkv, d)).astype(np.float64)
+    a[..., nd:] = 0.0
+    a /= np.linalg.norm(a, axis=-1, keepdims=True)
+    a32 = a.astype(np.float32)
+    for h in range(Hq):
+        q[:, h] += np.float32(w.beta) * a32[:, h // g]
+    K[:, :, 0, :] = np.float32(w.kappa * math.sqrt(d)) * a32
+    pos = _positional(w)
+    if pos is not None:
+        q[..., nd:] = pos[n_keys - 1][None, None]
+        K[..., nd:] = pos[None, None]
+    return {"q": f32_to_bf16_bits(q), "K": f32_to_bf16_bits(K), "V": f32_to_bf16_bits(V)}
+
+
+# decode step timed by bench.py beside the prefill headline: 32 query heads over 8 KV heads, 32K cached keys
+DECODE = Workload("decode32k", 4, 32, 8, 32768, 128, 128, 64, True)
+DECODE_SPLITS = 16
+
+
 def sample_blocks(w: Workload, n_random: int, seed: int = DEFAULT_SEED) -> np.ndarray:
     """Query blocks (b, h, i) used where a full-size CPU check is too slow: for the first
     and last (b, h) the first, last and quarter-point blocks, plus n_random drawn uniformly."""

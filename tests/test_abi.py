@@ -74,6 +74,23 @@ def test_bad_arguments_are_rejected_before_launch(pkg):
     assert va(*base, 0, 0, 0, 0, 1, 1, 0.0, 0.0, none, p, 1 << 20, none) == -1      # frozen max would stay -inf
     assert va(*base, 1, 1, 1, 0, 0, 0, 0.0, -1.0, none, p, 1 << 20, none) == -1     # negative threshold
     assert va(none, p, p, p, none, *ok_shape, 1, 1, 1, 0, 0, 0, 0.0, 0.0, none, p, 1 << 20, none) == -1
+    ap = lambda *a: L.vfa_kblock_summary_append(*a)
+    assert ap(p, p, 1, 1, 256, 10, 5, 128, 64, none) == -1                          # n_new < n_old
+    assert ap(p, p, 1, 1, 256, 0, 300, 128, 64, none) == -1                         # beyond the capacity
+    assert ap(p, p, 1, 1, 256, 5, 5, 128, 64, none) == 0                            # nothing appended: no-op
+    assert ap(none, p, 1, 1, 256, 0, 5, 128, 64, none) == -1
+    dc = lambda *a: L.vfa_decode_fwd(*a)
+    dshape = (1, 8, 2, 1024)                                                        # B, Hq, Hkv, n_cap
+    assert dc(p, p, p, p, p, none, *dshape, 0, 128, 64, 1, 1, 1, 4, 0.0, p, 1 << 20, none) == -1     # no keys
+    assert dc(p, p, p, p, p, none, *dshape, 2000, 128, 64, 1, 1, 1, 4, 0.0, p, 1 << 20, none) == -1  # n_keys > n_cap
+    assert dc(p, p, p, p, p, none, *dshape, 100, 128, 64, 0, 0, 0, 4, 0.0, p, 1 << 20, none) == -1   # max would stay -inf
+    assert dc(p, p, p, p, p, none, *dshape, 100, 128, 64, 1, 1, 1, 0, 0.0, p, 1 << 20, none) == -1   # n_splits < 1
+    assert dc(p, p, p, p, p, none, *dshape, 100, 128, 64, 1, 1, 1, 4, 0.0, p, 64, none) == -1        # workspace too small
+    assert dc(p, p, p, none, p, none, *dshape, 100, 128, 64, 1, 1, 1, 4, 0.0, p, 1 << 20, none) == -1  # summaries missing
+    assert dc(p, p, p, p, p, none, 1, 64, 1, 1024, 100, 128, 64, 1, 1, 1, 4, 0.0, p, 1 << 22, none) == -2  # 64 heads per KV head
+    assert dc(p, p, p, p, p, none, *dshape, 100, 128, 32, 1, 1, 1, 4, 0.0, p, 1 << 20, none) == -2   # block_n
+    assert dc(p, p, p, p, p, none, 0, 8, 2, 1024, 100, 128, 64, 1, 1, 1, 4, 0.0, p, 1 << 20, none) == 0
+    assert pkg.decode_workspace_bytes(1, 8, 128, 4) >= 1 * 8 * 4 * 130 * 4
     assert L.vfa_kblock_summary_mode(p, p, 1, 1, 64, 128, 64, 7, none) == -1
     assert L.vfa_kblock_summary_mode(none, p, 1, 1, 64, 128, 64, 2, none) == -1
     assert L.vfa_kblock_summary(none, p, 1, 1, 64, 128, 64, none) == -1

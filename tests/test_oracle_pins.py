@@ -502,6 +502,18 @@ def test_generators_are_seeded_and_structured(oracle):
     assert middle.mean() > 0.95 and np.median(S.max(1)) > 5.0
 
 
+def test_decode_generator_shares_the_cache_of_the_prefill_recipe():
+    w = wl.small(wl.DECODE, B=1, N=512)
+    a, b = wl.generate_decode(w, 300), wl.generate_decode(w, 300)
+    assert all(np.array_equal(a[k], b[k]) for k in a) and a["q"].shape == (1, 32, 128)
+    full = wl.generate(w)
+    assert np.array_equal(full["K"], a["K"]) and np.array_equal(full["V"], a["V"])
+    q, K = wl.bf16_bits_to_f32(a["q"]), wl.bf16_bits_to_f32(a["K"])
+    s = np.einsum("bhd,bhnd->bhn", q.reshape(1, 8, 4, 128)[:, :, 0], K[:, :, :300]) / math.sqrt(128)
+    assert (s[..., 0] > s[..., 1:250].max(-1)).mean() > 0.5      # the sink key usually carries the largest far logit
+    assert s[..., 299].mean() > s[..., 100:200].mean() + 0.5     # and the token's own position gets the local bonus
+
+
 def test_bf16_rounding_is_nearest_even():
     x = np.array([1.0, 1.00390625, 1.01171875, -1.00390625, 3.4e38, 1e-40, 0.0], np.float32)
     bits = wl.f32_to_bf16_bits(x)
