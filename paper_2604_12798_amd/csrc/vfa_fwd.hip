@@ -1100,9 +1100,13 @@ template <int D>
 __global__ __launch_bounds__(64) void decode_split_kernel(const DecodeParams p) {
     using T = Tile<D>;
     constexpr int DB = D / 32;
-    __shared__ __attribute__((aligned(16))) uint8_t smem[4 * T::BYTES];  // K[2], V[2]
+    // K is double buffered, V single buffered: 3 tiles = 48 KiB at d = 128, so three workgroups share a CU
+    // and keep three times (next K tile + this V tile) in flight, which is what an HBM-bound loop needs
+    __shared__ __attribute__((aligned(16))) uint8_t smem[3 * T::BYTES];
     uint8_t* const Ks = smem;
     uint8_t* const Vs = smem + 2 * T::BYTES;
+    constexpr int NI = BN / (1024 / T::ROWB);  // load instructions per tile (one wave)
+    constexpr int WAIT_ALL_BUT_ONE_TILE = 0x0F70 | (NI & 15) | ((NI >> 4) << 14);  // s_waitcnt vmcnt(NI)
     const int lane = threadIdx.x, ql = lane & 31, hh = lane >> 5;
     const int split = blockIdx.x, bh = blockIdx.y;
     int b, h;
@@ -1123,20 +1127,22 @@ __global__ __launch_bounds__(64) void decode_split_kernel(const DecodeParams p) 
     float lsum = 0.f;
     if (t_lo < t_hi) {
         load_tile<D, 1>(Kg, t_lo * BN, p.n_keys, Ks, false, 0, lane);
-        load_tile<D, 1>(Vg, t_lo * BN, p.n_keys, Vs, true, 0, lane);
         wait_vm0_and_sync();
     }
     for (int t = t_lo; t < t_hi; ++t) {
         const int cur = (t - t_lo) & 1;
-        if (t + 1 < t_hi) {
-            load_tile<D, 1>(Kg, (t + 1) * BN, p.n_keys, Ks + (cur ^ 1) * T::BYTES, false, 0, lane);
-            load_tile<D, 1>(Vg, (t + 1) * BN, p.n_keys, Vs + (cur ^ 1) * T::BYTES, true, 0, lane);
-        }
+        // the V buffer's last readers (the P.V MFMAs of the previous tile) have all issued
+        load_tile<D, 1>(Vg, t * BN, p.n_keys, Vs, true, 0, lane);
+        const bool more = t + 1 < t_hi;
+        if (more) load_tile<D, 1>(Kg, (t + 1) * BN, p.n_keys, Ks + (cur ^ 1) * T::BYTES, false, 0, lane);
         f32x16 st[2];
         uint32_t pk[16];
         qk_tile_pipe<D>(Ks + cur * T::BYTES, qf, st, ql, hh);
         softmax_tile<false, true, DB>(st, pk, ot, m2, lsum, p.c, t * BN, p.n_keys - 1, hh);  // frozen max, ragged tail masked
-        pv_tile_pipe<D>(Vs + cur * T::BYTES, pk, ot, lane, hh);
+        if (more) __builtin_amdgcn_s_waitcnt(WAIT_ALL_BUT_ONE_TILE);  // V(t) has landed; K(t + 1) may still be on its way
+        else __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        pv_tile_pipe<D>(Vs, pk, ot, lane, hh);
         wait_vm0_and_sync();
     }
     const float l = xhalf_sum(lsum);
