@@ -48,6 +48,7 @@ struct Params {
     uint8_t* mask;
     int B, Hq, Hkv, N, Tr, Tc;
     int causal, n_sink, n_local, use_minit;
+    int pair_blocks;  // ping-pong kernel: the two wave groups take two adjacent query blocks of one head (else two heads)
     int order_asc;    // ablation: visit key blocks in ascending order (sink / local blocks keep the exact-max update)
     int all_special;  // ablation: exact-max update on every visited block
     float c;     // softmax scale * log2(e)
@@ -100,9 +101,11 @@ __device__ inline uint32_t pack_bf16(float a, float b) {
 // remaining visible tiles ascending.  The first n_special visits take the exact-max update.
 struct Visit {
     int n1, s2, n2, total, n_special;
+    int n2b;  // block-pair VSA: the last n2b local tiles belong to the second query block and are visited first
     int m1, ms2, mn2;  // ascending-order ablation: tiles [0, m1) and [ms2, ms2 + mn2) are the sink / local ones
     __device__ int tile(int k) const {  // branch-free: this sits on the scalar unit in front of every tile fetch
-        const int lead = k < n1 ? k : s2 + (k - n1);
+        const int r = k - n1;
+        const int lead = k < n1 ? k : (r < n2b ? s2 + (n2 - n2b) + r : s2 + (r - n2b));
         int tail = k - n2;                                  // = n1 + (k - n1 - n2)
         tail += (n2 > 0 && tail >= s2) ? n2 : 0;
         return k < n1 + n2 ? lead : tail;
@@ -113,7 +116,7 @@ struct Visit {
 template <int MODE>
 __device__ inline Visit make_visit(const Params& p, int a_lo, int a_hi, int j_hi) {
     Visit vis;
-    vis.n1 = 0; vis.s2 = 0; vis.n2 = 0;
+    vis.n1 = 0; vis.s2 = 0; vis.n2 = 0; vis.n2b = 0;
     vis.m1 = 0; vis.ms2 = 0; vis.mn2 = 0;
     vis.total = j_hi + 1;
     if (is_fa(MODE)) {
@@ -551,23 +554,31 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
     const int ql = lane & 31;
     const int hh = lane >> 5;
 
-    const int g = p.Hq / p.Hkv, gp = g >> 1;
+    // Two ways to pair the groups (p.pair_blocks): 0 = two query heads of one KV head at the same query
+    // block (needs an even number of heads per KV head); 1 = the same head at two adjacent query blocks,
+    // a 256-row super-block.  In the second form the workgroup-level geometry below spans both blocks,
+    // so the visit list is the union of what the two blocks need: the local set covers both diagonals,
+    // and under a causal mask the first group finds the second group's diagonal tiles fully masked
+    // (exp gives 0; two wasted tiles per workgroup).  Only h, the rows and the m-init range are per group.
+    const int pb = p.pair_blocks;
+    const int g = p.Hq / p.Hkv, gp = pb ? g : g >> 1;  // units (heads or head pairs) per KV head
+    const int Ti = pb ? (p.Tr + 1) >> 1 : p.Tr;        // query blocks or super-blocks
     const int G = p.B * p.Hkv;
     int b, hkv, hp, i;
     {
         const int id = blockIdx.x;
         if ((G & 7) == 0) {
             const int x = id & 7, y = id >> 3;
-            const int per = p.Tr * gp;
+            const int per = Ti * gp;
             const int kvl = y / per, rem = y - kvl * per;
-            i = p.Tr - 1 - rem / gp;
+            i = Ti - 1 - rem / gp;
             hp = rem % gp;
             const int kv = kvl * 8 + x;
             b = kv / p.Hkv;
             hkv = kv - b * p.Hkv;
         } else {
             const int per = G * gp;
-            i = p.Tr - 1 - id / per;
+            i = Ti - 1 - id / per;
             const int rem = id % per;
             hp = rem % gp;
             const int kv = rem / gp;
@@ -575,18 +586,21 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
             hkv = kv - b * p.Hkv;
         }
     }
-    const int h = hkv * g + 2 * hp + grp;
+    const int h = pb ? hkv * g + hp : hkv * g + 2 * hp + grp;
     const int N = p.N;
-    const int row0 = i * BM;
-    const int last_row = min(N, row0 + BM) - 1;
+    const int row0 = (pb ? 2 * i : i) * BM;                      // first row of the workgroup
+    const int last_row = min(N, row0 + (pb ? 2 * BM : BM)) - 1;  // last row of the workgroup
     const int a_lo = row0 / BN, a_hi = last_row / BN;
     const int j_hi = p.causal ? a_hi : p.Tc - 1;
+    const int row0_g = row0 + (pb ? grp * BM : 0);               // first row of this group
+    // last key block this group's rows can see (a group past the end of the sequence mirrors row N - 1)
+    const int j_hi_g = p.causal ? (min(N, row0_g + BM) - 1) / BN : p.Tc - 1;
 
     const uint16_t* Qg = p.Q + ((size_t)(b * p.Hq + h) * N) * D;
     const uint16_t* Kg = p.K + ((size_t)(b * p.Hkv + hkv) * N) * D;
     const uint16_t* Vg = p.V + ((size_t)(b * p.Hkv + hkv) * N) * D;
 
-    const int qrow = row0 + 32 * w4 + ql;
+    const int qrow = row0_g + 32 * w4 + ql;
     const int qrow_c = min(qrow, N - 1);
     const int limit = p.causal ? qrow_c : N - 1;
     bf16x8 qf[KK];
@@ -610,19 +624,28 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
             for (int u = 0; u < nb; ++u) {
                 f32x16 st[2];
                 qk_tile<D>(pp_smem + u * T::BYTES, qf, st, ql, hh);
-                mx = fmaxf(mx, tile_rowmax<true>(st, (t0 + u) * BN, j_hi, hh));
+                mx = fmaxf(mx, tile_rowmax<true>(st, (t0 + u) * BN, j_hi_g, hh));
             }
         }
         m2 = xhalf_max(mx) * p.c;
         __syncthreads();
     }
 
-    const Visit vis = make_visit<MODE>(p, a_lo, a_hi, j_hi);
+    Visit vis = make_visit<MODE>(p, a_lo, a_hi, j_hi);
+    if (MODE == MODE_VSA && pb) {
+        // Block pairs under Alg. 2 (causal, at most one local block per query block): the second block's
+        // local tiles come first (exact-max for group 1, invisible to group 0), then the first block's
+        // (exact-max for group 0, ordinary frozen tiles for group 1, whose max is final by then), so each
+        // group meets its own tiles in the order Alg. 2 gives them and takes the same skip decisions.
+        const int lo_b = (row0 + BM) / BN;  // first tile of the second block's diagonal
+        vis.n2b = vis.n2 > 0 ? max(0, vis.s2 + vis.n2 - max(vis.s2, lo_b)) : 0;
+    }
     const int nv = vis.total;
     uint8_t* mrow = nullptr;
-    if (MODE == MODE_VSA && p.mask) {
-        mrow = p.mask + ((size_t)(b * p.Hq + h) * p.Tr + i) * p.Tc;
-        for (int j = j_hi + 1 + (tid & 255); j < p.Tc; j += 256) mrow[j] = 2;
+    const int i_blk = pb ? 2 * i + grp : i;  // this group's query block
+    if (MODE == MODE_VSA && p.mask && i_blk < p.Tr) {
+        mrow = p.mask + ((size_t)(b * p.Hq + h) * p.Tr + i_blk) * p.Tc;
+        for (int j = j_hi_g + 1 + (tid & 255); j < p.Tc; j += 256) mrow[j] = 2;
     }
 
     f32x16 ot[DB];
@@ -803,7 +826,7 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
         if (MODE == MODE_VSA) {
             keep = __builtin_amdgcn_readfirstlane(votes[k & 1][grp][0] | votes[k & 1][grp][1] | votes[k & 1][grp][2] |
                                                   votes[k & 1][grp][3]) != 0;  // same for every lane: say so
-            if (mrow && (tid & 255) == 0) mrow[j] = keep ? 0 : 1;
+            if (mrow && j <= j_hi_g && (tid & 255) == 0) mrow[j] = keep ? 0 : 1;  // (a tile past j_hi_g is the other block's)
         }
         pv_pending = keep;
         if (keep) {
@@ -916,7 +939,9 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
         for (; k < min(n_lead, nv); ++k) {
             matrix_any(k);
             __builtin_amdgcn_s_barrier();
-            vector_phase(k, true_type{}, false_type{}, false_type{});
+            // block pairs: a local tile is exact-max only for the group whose block it belongs to
+            if (!pb || k < vis.n1 || ((k - vis.n1 < vis.n2b) == (grp == 1))) vector_phase(k, true_type{}, false_type{}, false_type{});
+            else vector_phase(k, false_type{}, false_type{}, false_type{});
             __builtin_amdgcn_s_barrier();
         }
         for (; k < nv; ++k) {
@@ -1196,7 +1221,12 @@ template <int MODE>
 int launch_fwd(const Params& p, int d, int block_m, hipStream_t s) {
     (void)hipGetLastError();
     const int g = p.Hq / p.Hkv;
-    if (d == 128 && block_m == 128 && (g & 1) == 0 && !p.order_asc && !p.all_special) {
+    // ping-pong kernel: head pairs when the heads per KV head are even; otherwise (MHA, odd groups) pairs of
+    // adjacent query blocks; for VSA only where each block still meets its tiles in Alg. 2's order
+    // (causal, at most one local block), since the skip decisions depend on the max at the time of the visit
+    const bool head_pairs = (g & 1) == 0;
+    if (d == 128 && block_m == 128 && !p.order_asc && !p.all_special &&
+        (head_pairs || MODE != MODE_VSA || (p.causal && p.n_local <= 1))) {
         static bool attr_set = false;  // opt in to more than 64 KB of LDS once per instantiation
         if (!attr_set) {
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_pp_kernel<MODE>),
@@ -1204,8 +1234,10 @@ int launch_fwd(const Params& p, int d, int block_m, hipStream_t s) {
                 return VFA_ERR_HIP;
             attr_set = true;
         }
-        const dim3 grid_pp((unsigned)(p.B * (p.Hq / 2) * p.Tr));
-        attn_fwd_pp_kernel<MODE><<<grid_pp, 512, PP_LDS_BYTES, s>>>(p);
+        Params q = p;
+        q.pair_blocks = head_pairs ? 0 : 1;
+        const dim3 grid_pp((unsigned)(head_pairs ? p.B * (p.Hq / 2) * p.Tr : p.B * p.Hq * ((p.Tr + 1) / 2)));
+        attn_fwd_pp_kernel<MODE><<<grid_pp, 512, PP_LDS_BYTES, s>>>(q);
         return hipGetLastError() == hipSuccess ? VFA_OK : VFA_ERR_HIP;
     }
     const dim3 grid((unsigned)(p.B * p.Hq * p.Tr));

@@ -39,6 +39,9 @@ SMALL = [
     ("sink0_local2_noncausal", W(B=1, Hq=1, Hkv=1, N=896, n_sink=0, n_local=2, causal=False)),
     ("sink1_local0", W(B=1, Hq=1, Hkv=1, N=768, n_sink=1, n_local=0)),
     ("planted_noncausal", W("cfg4", B=1, Hq=2, Hkv=2, N=2048)),
+    # odd number of query heads per KV head: the ping-pong kernel pairs adjacent query blocks (odd block count, ragged)
+    ("gqa3_ragged_1100", W(B=1, Hq=3, Hkv=1, N=1100)),
+    ("mha_causal_1280_sink2_local2", W(B=2, Hq=2, Hkv=2, N=1280, n_sink=2, n_local=2)),
 ]
 
 
@@ -110,6 +113,11 @@ VSA_CASES = [
     ("noncausal_thr5", W(B=1, Hq=2, Hkv=2, N=1024, beta=6.0, kappa=3.0, causal=False), 5.0),
     ("ragged_thr4", W(B=1, Hq=2, Hkv=1, N=1000, beta=6.0, kappa=3.0), 4.0),
     ("d64_64x64_thr4", W(B=1, Hq=2, Hkv=1, N=1024, d=64, F=4, block_m=64, beta=6.0, kappa=3.0), 4.0),
+    # one query head per KV head, causal: two adjacent query blocks share a workgroup (odd block count: one is alone)
+    ("mha_causal_thr4_17blocks", W(B=1, Hq=2, Hkv=2, N=2176, beta=6.0, kappa=3.0), 4.0),
+    ("gqa3_causal_thr6_ragged", W(B=1, Hq=3, Hkv=1, N=1900, beta=6.0, kappa=3.0), 6.0),
+    ("mha_causal_thr4_no_local", W(B=1, Hq=2, Hkv=2, N=1024, beta=6.0, kappa=3.0, n_local=0), 4.0),
+    ("mha_causal_thr4_local2_generic", W(B=1, Hq=2, Hkv=2, N=1024, beta=6.0, kappa=3.0, n_local=2), 4.0),
 ]
 
 
