@@ -161,8 +161,8 @@ def main():
     if "vfa" in only:
         ms_k = time_region(run_vfa_kernel_only, args.steps, args.warmup)
         g = w.Hq // w.Hkv
-        kernel = ("attn_fwd_pp_kernel<VFA>" if (w.d == 128 and w.block_m == 128 and g % 2 == 0)
-                  else f"attn_fwd_kernel<{w.d},{w.block_m // 32},VFA>")
+        kernel = ("attn_fwd_pp_kernel<VFA>" + (" (head pairs)" if g % 2 == 0 else " (block pairs)")
+                  if (w.d == 128 and w.block_m == 128) else f"attn_fwd_kernel<{w.d},{w.block_m // 32},VFA>")
         out["roofline"] = {"bound": "mfma", "kernel": kernel, "achieved": dense / ms_k / 1e9,
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": dense / ms_k / 1e9 / MFMA_BF16_PEAK_TFLOPS,
                            # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (profiles/attn_fwd_cfg3.md)
