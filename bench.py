@@ -111,7 +111,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is a single-GPU kernel path; run it with --gpus 1 "
-              "(sharding over (batch, KV head) needs no communication and is described in DESIGN.md)", file=sys.stderr)
+              "(the path shards over (batch, KV head) without communication; more than one GPU is not run here)", file=sys.stderr)
         sys.exit(2)
 
     import torch

@@ -21,6 +21,11 @@
  * Return value: VFA_OK, or a negative code; vfa_strerror() names it.  Nothing is launched
  * when a negative code is returned, except VFA_ERR_HIP (a launch itself failed).
  * The functions never throw, abort or print.  Same inputs give bit-identical outputs.
+ *
+ * Calls may be recorded into a HIP graph (they only enqueue kernels; nothing is allocated, copied
+ * or cleared).  One exception: the first launch of an attention kernel that needs more than 64 KiB
+ * of LDS (d = 128 with block_m = 128) sets that function attribute, so make one ordinary call per
+ * entry point and process before capturing.
  */
 #ifndef VFA_H_
 #define VFA_H_

@@ -210,3 +210,32 @@ def test_custom_scale_and_no_lse(vfa, oracle):
     assert L2 is None and torch.equal(O, O2)
     ref = oracle.blocks(Qh, Kh, Vh, 128, 64, True, blocks, scale=0.05)
     check_o_lse(O, L, ref["O"], ref["LSE"], blocks, 128, 512, "custom scale")
+
+
+def test_graph_capture_and_side_stream(vfa, oracle):
+    """The entry points only enqueue kernels on the given stream (no allocation, no synchronisation), so
+    they can be captured into a HIP graph and replayed, and run on a stream other than the default one."""
+    import torch
+    w = W(B=1, Hq=4, Hkv=2, N=1024)
+    t = wl.generate(w)
+    Q, K, V = gpu_inputs(t)
+    kw = dict(block_m=w.block_m, block_n=w.block_n, causal=w.causal)
+    ws = torch.empty(vfa.workspace_bytes(w.B, w.Hkv, w.N, w.d, w.block_n), dtype=torch.uint8, device="cuda")
+    O0, L0 = vfa.vfa_attn_fwd(Q, K, V, workspace=ws, **kw)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    O1, L1 = torch.empty_like(O0), torch.empty_like(L0)
+    with torch.cuda.stream(side):
+        vfa.vfa_attn_fwd(Q, K, V, workspace=ws, out=O1, lse=L1, **kw)
+    side.synchronize()
+    assert torch.equal(O0, O1) and torch.equal(L0, L1)
+    O2, L2 = torch.empty_like(O0), torch.empty_like(L0)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        vfa.vfa_attn_fwd(Q, K, V, workspace=ws, out=O2, lse=L2, **kw)
+    for rep in range(3):
+        O2.zero_(); L2.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(O0, O2) and torch.equal(L0, L2), rep
