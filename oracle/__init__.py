@@ -165,6 +165,27 @@ def fa_lazy(Q, K, V, block_m, block_n, causal, blocks_, tau, scale=None):
     return dict(O=O, LSE=L, counters=cnt)
 
 
+def blasst_variant(Q, K, V, block_m, block_n, causal, blocks_, skip_threshold_nats, *, rowskip=False, lazy_tau=None,
+                   scale=None):
+    """Blasst_Rowskip (rowskip=True) or Blasst_FA4 (lazy_tau >= 0) of the appendix; with neither, vanilla BLASST.
+    Returns dict O, LSE, mask, margin, counters."""
+    Q, K, V = _f32(Q), _f32(K), _f32(V)
+    B, Hq, Hkv, N, d = _dims(Q, K)
+    scale = 1.0 / math.sqrt(d) if scale is None else scale
+    Tc = -(-N // block_n)
+    blk = np.ascontiguousarray(blocks_, dtype=np.int32)
+    n = len(blk)
+    O = np.full((n, block_m, d), np.nan); L = np.full((n, block_m), np.nan)
+    mask = np.zeros((n, Tc), dtype=np.uint8); margin = np.empty((n, Tc)); cnt = np.zeros((n, 4), dtype=np.int64)
+    rc = _load().oracle_blasst_variant(
+        _p(Q, ctypes.c_float), _p(K, ctypes.c_float), _p(V, ctypes.c_float), B, Hq, Hkv, N, d, block_m, block_n,
+        int(causal), ctypes.c_double(scale), ctypes.c_double(-float(skip_threshold_nats)), int(bool(rowskip)),
+        ctypes.c_double(-1.0 if lazy_tau is None else float(lazy_tau)), n, _p(blk, ctypes.c_int), _p(O, ctypes.c_double),
+        _p(L, ctypes.c_double), _p(mask, ctypes.c_uint8), _p(margin, ctypes.c_double), _p(cnt, ctypes.c_int64))
+    assert rc == 0
+    return dict(O=O, LSE=L, mask=mask, margin=margin, counters=cnt)
+
+
 def decode(q, K, V, n_keys, block_n, *, n_sink=1, n_local=1, use_minit=True, n_parts=1, scale=None):
     """One query token per head against the first n_keys rows of a K/V cache [B,Hkv,n_cap,d].
     Returns dict O [B,Hq,d], LSE, m_init, m_final [B,Hq], l_parts [B,Hq,n_parts]."""

@@ -235,6 +235,7 @@ typedef struct {
     int n_sink, n_local, use_minit, reorder, freeze, vsa;
     double ln_lambda;
     double lazy_tau; /* < 0: off; else keep the old max while it grows by at most lazy_tau * ln 2 */
+    int rowskip;     /* with vsa: rows that fail the threshold test drop out of a kept tile */
 } opts_t;
 
 static void one_block(const prob_t *p, const opts_t *o, const double *krepr, int b, int h, int i,
@@ -307,8 +308,21 @@ static void one_block(const prob_t *p, const opts_t *o, const double *krepr, int
             if (worst < o->ln_lambda) {
                 if (mask_row) mask_row[j] = 1;
                 counters[3] += 1; /* skipped tiles */
+                if (o->rowskip) counters[2] += nr; /* (row-skip runs report suppressed rows here) */
                 if (traj) for (int rr = 0; rr < nr; ++rr) { traj[((size_t)k * Br + rr) * 2] = m[rr]; traj[((size_t)k * Br + rr) * 2 + 1] = l[rr]; }
                 continue;
+            }
+            if (o->rowskip) {
+                /* Blasst_Rowskip: in a tile that is kept, a row that fails the same test contributes
+                 * nothing: its scores become -inf (zero mass) and its state does not move */
+                for (int rr = 0; rr < nr; ++rr) {
+                    const double diff = (mt[rr] == -INFINITY) ? -INFINITY : mt[rr] - fmax(m[rr], mt[rr]);
+                    if (diff < o->ln_lambda) {
+                        for (int cc = 0; cc < nc; ++cc) S[rr * Bc + cc] = -INFINITY;
+                        mt[rr] = -INFINITY;
+                        counters[2] += 1;
+                    }
+                }
             }
         }
         if (mask_row) mask_row[j] = 0;
@@ -324,7 +338,7 @@ static void one_block(const prob_t *p, const opts_t *o, const double *krepr, int
                 else if (m_new != m[rr]) any = 1;
             }
             counters[2] += any;
-        } else if (special) {
+        } else if (special && !o->rowskip) {
             counters[2] += 1; /* rescale chain executed on this tile */
         }
         for (int rr = 0; rr < nr; ++rr) {
@@ -388,7 +402,7 @@ int oracle_blocks(const float *Q, const float *K, const float *V, int B, int Hq,
     if (Hq % Hkv != 0 || block_m <= 0 || block_n <= 0) return -1;
     if (use_minit && !krepr && !m_override) return -1;
     prob_t p = {Q, K, V, B, Hq, Hkv, N, d, block_m, block_n, causal, scale};
-    opts_t o = {n_sink, n_local, use_minit, reorder, freeze, vsa, ln_lambda, -1.0};
+    opts_t o = {n_sink, n_local, use_minit, reorder, freeze, vsa, ln_lambda, -1.0, 0};
     const int Tc = ceil_div(N, block_n);
 #pragma omp parallel for schedule(dynamic, 1)
     for (int n = 0; n < nblk; ++n) {
@@ -417,7 +431,7 @@ int oracle_fa_lazy(const float *Q, const float *K, const float *V, int B, int Hq
                    const int *blocks, double *O, double *LSE, int64_t *counters) {
     if (Hq % Hkv != 0 || block_m <= 0 || block_n <= 0 || !(tau >= 0.0)) return -1;
     prob_t p = {Q, K, V, B, Hq, Hkv, N, d, block_m, block_n, causal, scale};
-    opts_t o = {0, 0, 0, 0, 0, 0, 0.0, tau};
+    opts_t o = {0, 0, 0, 0, 0, 0, 0.0, tau, 0};
 #pragma omp parallel for schedule(dynamic, 1)
     for (int n = 0; n < nblk; ++n) {
         int64_t *cn = counters + (size_t)n * 4;
@@ -494,6 +508,37 @@ int oracle_decode(const float *q, const float *K, const float *V, int B, int Hq,
         if (m_init) m_init[bh] = mi;
         if (m_final) m_final[bh] = mf;
         free(s);
+    }
+    return 0;
+}
+
+/* The two remaining skip variants of the appendix, both in ascending order with the exact-max
+ * update on every block and no m-init (as vanilla BLASST):
+ *   rowskip = 1  Blasst_Rowskip: a tile is skipped only if no row passes the threshold test; in a
+ *                kept tile the rows that fail it are suppressed (scores -inf, state untouched).
+ *                counters[2] = suppressed rows (the variant's row-wise sparsity numerator)
+ *   lazy_tau >= 0  Blasst_FA4: block skip first, then on kept tiles a row keeps its old max while
+ *                the new one exceeds it by at most lazy_tau * ln 2.  counters[2] = tiles whose
+ *                rescale chain ran
+ * counters [nblk, 4] as in oracle_blocks otherwise; mask_out / margin_out as there.            */
+int oracle_blasst_variant(const float *Q, const float *K, const float *V, int B, int Hq, int Hkv,
+                          int N, int d, int block_m, int block_n, int causal, double scale,
+                          double ln_lambda, int rowskip, double lazy_tau, int nblk, const int *blocks,
+                          double *O, double *LSE, uint8_t *mask_out, double *margin_out,
+                          int64_t *counters) {
+    if (Hq % Hkv != 0 || block_m <= 0 || block_n <= 0 || !(ln_lambda < 0.0)) return -1;
+    if (rowskip && lazy_tau >= 0.0) return -1;
+    prob_t p = {Q, K, V, B, Hq, Hkv, N, d, block_m, block_n, causal, scale};
+    opts_t o = {0, 0, 0, 0, 0, 1, ln_lambda, lazy_tau, rowskip};
+    const int Tc = ceil_div(N, block_n);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int n = 0; n < nblk; ++n) {
+        int64_t *cn = counters + (size_t)n * 4;
+        cn[0] = cn[1] = cn[2] = cn[3] = 0;
+        one_block(&p, &o, NULL, blocks[3 * n], blocks[3 * n + 1], blocks[3 * n + 2], NULL,
+                  O + (size_t)n * block_m * d, LSE + (size_t)n * block_m, NULL, NULL,
+                  mask_out ? mask_out + (size_t)n * Tc : NULL,
+                  margin_out ? margin_out + (size_t)n * Tc : NULL, cn, NULL);
     }
     return 0;
 }

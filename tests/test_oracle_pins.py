@@ -443,6 +443,68 @@ def test_blasst_vanilla_mask_from_score_matrix(oracle):
     assert (out["mask"] == 1).any() and (out["mask"] == 0).any()
 
 
+@pytest.mark.parametrize("causal", [False, True])
+def test_rowskip_and_fa4_skip_variants(oracle, causal):
+    """Appendix variants Blasst_Rowskip and Blasst_FA4.  The decision rules are replayed on the full
+    score matrix; what the variants then compute must be library softmax over exactly the entries
+    they kept (for any choice of max), and the counters must count what the paper reports for them."""
+    w, Q, K, V = _vsa_problem(seed=33, causal=causal)
+    thr, tau, bm, bn = 3.0, 1.5, 32, 16
+    blocks = wl.all_blocks(w)
+    vanilla = oracle.blasst_variant(Q, K, V, bm, bn, causal, blocks, thr)
+    same = oracle.blocks(Q, K, V, bm, bn, causal, blocks, n_sink=0, n_local=0, use_minit=False, reorder=False,
+                         freeze=False, vsa=True, skip_threshold_nats=thr)
+    assert np.array_equal(vanilla["O"], same["O"]) and np.array_equal(vanilla["mask"], same["mask"])
+    rs = oracle.blasst_variant(Q, K, V, bm, bn, causal, blocks, thr, rowskip=True)
+    f4 = oracle.blasst_variant(Q, K, V, bm, bn, causal, blocks, thr, lazy_tau=tau)
+    suppressed_any = rescales_saved = 0
+    for n, (b, h, i) in enumerate(blocks):
+        _, _, _, S = lib_attention(Q[b, h], K[b, 0], V[b, 0], causal, w.scale)
+        rows = S[i * bm:(i + 1) * bm]
+        Vd = V[b, 0].astype(np.float64)
+        n_tiles = ((i * bm + bm - 1) // bn + 1) if causal else w.Tc
+        # --- row skip
+        m = np.full(bm, -np.inf); keep_entry = np.zeros_like(rows, dtype=bool); mask = np.full(w.Tc, 2); supp = 0
+        for j in range(n_tiles):
+            mt = rows[:, j * bn:(j + 1) * bn].max(1)
+            with np.errstate(invalid="ignore"):
+                ok = np.where(np.isneginf(mt), False, mt - np.maximum(m, mt) >= -thr)
+            mask[j] = 0 if ok.any() else 1
+            supp += int((~ok).sum())
+            if ok.any():
+                keep_entry[ok, j * bn:(j + 1) * bn] = True
+                m = np.where(ok, np.maximum(m, mt), m)
+        assert np.array_equal(rs["mask"][n], mask) and rs["counters"][n, 2] == supp
+        for r in range(bm):
+            sel = keep_entry[r] & np.isfinite(rows[r])
+            want = scipy.special.softmax(rows[r, sel]) @ Vd[sel]
+            assert np.abs(rs["O"][n, r] - want).max() < 1e-12
+            assert abs(rs["LSE"][n, r] - scipy.special.logsumexp(rows[r, sel])) < 1e-12
+        suppressed_any += supp
+        # --- block skip, then conditional rescale against the lagging max
+        m = np.full(bm, -np.inf); kept_tiles = []; mask = np.full(w.Tc, 2); ran = 0
+        for j in range(n_tiles):
+            mt = rows[:, j * bn:(j + 1) * bn].max(1)
+            with np.errstate(invalid="ignore"):
+                ok = np.where(np.isneginf(mt), False, mt - np.maximum(m, mt) >= -thr)
+            mask[j] = 0 if ok.any() else 1
+            if ok.any():
+                kept_tiles.append(j)
+                new = np.maximum(m, mt)
+                with np.errstate(invalid="ignore"):
+                    lag = (~np.isneginf(m)) & (new - m <= tau * math.log(2))
+                new = np.where(lag, m, new)
+                ran += int((new != m).any())
+                m = new
+        assert np.array_equal(f4["mask"][n], mask) and f4["counters"][n, 2] == ran
+        cols = np.concatenate([np.arange(j * bn, (j + 1) * bn) for j in kept_tiles])
+        for r in range(bm):
+            sel = cols[np.isfinite(rows[r, cols])]
+            assert np.abs(f4["O"][n, r] - scipy.special.softmax(rows[r, sel]) @ Vd[sel]).max() < 1e-12
+        rescales_saved += len(kept_tiles) - ran
+    assert suppressed_any > 0 and rescales_saved > 0 and (rs["mask"] == 1).any()
+
+
 def test_vsa_mask_uses_frozen_max(oracle):
     """Alg. 2 with freeze: on non-special tiles the test compares against
     m = max(m_init, rowmax of the special tiles that were kept)."""
