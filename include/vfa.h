@@ -109,7 +109,7 @@ int vsa_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LS
 
 /* VFA / VSA with the switches of the ablation study and of the sparse-attention variants
  * (Experiments: "Ablating the k_repr construction", "Removing m-initialization", "Ablating the
- * reordered schedule"; appendix: variants Blasst and Blasst_SWA).  As vfa_attn_fwd / vsa_attn_fwd,
+ * reordered schedule"; appendix: variants Blasst, Blasst_SWA, Blasst_Rowskip, Blasst_FA4).  As vfa_attn_fwd / vsa_attn_fwd,
  * plus:
  *   repr_mode  block representation used when use_minit == 1 (see vfa_kblock_summary_mode)
  *   reorder    1 = sink blocks, local blocks, then the rest (the method); 0 = ascending block
@@ -117,15 +117,21 @@ int vsa_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LS
  *   freeze     1 = exact-max update on sink / local blocks only (the method); 0 = on every
  *              block (then n_sink = n_local = 0 with use_minit = 0 is allowed)
  *   skip_threshold_nats  0 = no block skipping (skip_mask ignored); > 0 = the Alg. 2 skip test.
- * reorder = freeze = 1, repr_mode = 0 is exactly vfa_attn_fwd / vsa_attn_fwd.  Vanilla BLASST is
- * (use_minit 0, reorder 0, freeze 0, threshold > 0); Blasst_SWA is the same with reorder 1.
+ *   rowskip    1 = Blasst_Rowskip: in a tile that is kept, a row that fails the threshold test is
+ *              suppressed (scores -inf, its state untouched); needs skipping and freeze = 0
+ *   lazy_rescale_tau  >= 0 = Blasst_FA4: on kept tiles a row keeps its old max while the new one
+ *              exceeds it by at most tau * ln 2; negative = off; needs skipping and freeze = 0
+ * reorder = freeze = 1, repr_mode = 0, rowskip = 0, tau < 0 is exactly vfa_attn_fwd / vsa_attn_fwd.
+ * Vanilla BLASST is (use_minit 0, reorder 0, freeze 0, threshold > 0); Blasst_SWA is the same with
+ * reorder 1.
  * Every setting without skipping is exact attention; they differ in how far the frozen max sits
  * from the true one, which is what the ablation measures.  These run on the generic kernel. */
 int vfa_variant_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
                     int Hq, int Hkv, int N, int d, int block_m, int block_n, int causal,
                     int n_sink, int n_local, int use_minit, int repr_mode, int reorder, int freeze,
-                    float softmax_scale, float skip_threshold_nats, unsigned char* skip_mask,
-                    void* workspace, size_t workspace_bytes, void* stream);
+                    int rowskip, float lazy_rescale_tau, float softmax_scale,
+                    float skip_threshold_nats, unsigned char* skip_mask, void* workspace,
+                    size_t workspace_bytes, void* stream);
 
 /* Summaries of a growing key cache (Methods, Step 1: "for decoding with a growing KV-cache, this
  * precomputation can be performed incrementally for newly appended key blocks").  K is a cache

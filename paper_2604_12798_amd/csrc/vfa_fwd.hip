@@ -51,6 +51,7 @@ struct Params {
     int pair_blocks;  // ping-pong kernel: the two wave groups take two adjacent query blocks of one head (else two heads)
     int order_asc;    // ablation: visit key blocks in ascending order (sink / local blocks keep the exact-max update)
     int all_special;  // ablation: exact-max update on every visited block
+    int rowskip;      // skip variant: in a kept tile, rows that fail the threshold test are suppressed (generic kernel)
     float c;     // softmax scale * log2(e)
     float thr2;  // skip threshold in log2 units
     float tau2;  // MODE_FA_LAZY: a row keeps its old max while the new one exceeds it by at most tau2 (log2 units)
@@ -505,12 +506,21 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const Params p) {
             for (int w = 0; w < NW; ++w) any |= votes[buf][w];
             keep = any != 0;
             if (p.mask && tid == 0) p.mask[((size_t)(b * p.Hq + h) * p.Tr + i) * p.Tc + j] = keep ? 0 : 1;
+            if (p.rowskip && keep) {  // row-level variant: a row that failed the test contributes nothing to a kept tile
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) st[t][r] = row_keeps ? st[t][r] : -INFINITY;
+            }
         }
         if (keep) {
             uint32_t pk[16];
             if (special) {
-                if (masked) softmax_tile<true, true, DB, true, MODE == MODE_FA_LAZY>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh, p.tau2);
-                else softmax_tile<true, false, DB, true, MODE == MODE_FA_LAZY>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh, p.tau2);
+                // (VSA takes the conditional-rescale form too; its tau2 is negative unless the variant asks for it,
+                // and then only the branch over an all-ones rescale is left of it)
+                constexpr bool LAZY = MODE == MODE_FA_LAZY || MODE == MODE_VSA;
+                if (masked) softmax_tile<true, true, DB, true, LAZY>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh, p.tau2);
+                else softmax_tile<true, false, DB, true, LAZY>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh, p.tau2);
             } else {
                 if (masked) softmax_tile<false, true, DB>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh);
                 else softmax_tile<false, false, DB>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh);
@@ -1225,7 +1235,7 @@ int launch_fwd(const Params& p, int d, int block_m, hipStream_t s) {
     // adjacent query blocks; for VSA only where each block still meets its tiles in Alg. 2's order
     // (causal, at most one local block), since the skip decisions depend on the max at the time of the visit
     const bool head_pairs = (g & 1) == 0;
-    if (d == 128 && block_m == 128 && !p.order_asc && !p.all_special &&
+    if (d == 128 && block_m == 128 && !p.order_asc && !p.all_special && !p.rowskip && !(MODE == MODE_VSA && p.tau2 >= 0.f) &&
         (head_pairs || MODE != MODE_VSA || (p.causal && p.n_local <= 1))) {
         static bool attr_set = false;  // opt in to more than 64 KB of LDS once per instantiation
         if (!attr_set) {
@@ -1268,12 +1278,16 @@ int summary_launch(const void* K, void* Krepr, int B, int Hkv, int N, int d, int
 int vfa_vsa_common(int mode, const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv,
                    int N, int d, int block_m, int block_n, int causal, int n_sink, int n_local, int use_minit,
                    float softmax_scale, float thr_nats, unsigned char* skip_mask, void* workspace,
-                   size_t workspace_bytes, void* stream, int repr_mode = 0, int reorder = 1, int freeze = 1) {
+                   size_t workspace_bytes, void* stream, int repr_mode = 0, int reorder = 1, int freeze = 1,
+                   int rowskip = 0, float lazy_tau = -1.f) {
     int rc = check_common(Q, K, V, O, LSE, B, Hq, Hkv, N, d, block_m, block_n);
     if (rc != VFA_OK) return rc;
     if (n_sink < 0 || n_local < 0) return VFA_ERR_INVALID_ARG;
     if (!use_minit && n_sink + n_local == 0 && freeze) return VFA_ERR_INVALID_ARG;
     if (repr_mode < 0 || repr_mode > 3) return VFA_ERR_INVALID_ARG;
+    if (!(lazy_tau < 0.f) && !isfinite(lazy_tau)) return VFA_ERR_INVALID_ARG;   // negative = off; NaN / inf rejected
+    if (lazy_tau != lazy_tau) return VFA_ERR_INVALID_ARG;
+    if ((rowskip || lazy_tau >= 0.f) && (mode != MODE_VSA || freeze)) return VFA_ERR_INVALID_ARG;
     if (mode == MODE_VSA && !(thr_nats > 0.f && isfinite(thr_nats))) return VFA_ERR_INVALID_ARG;
     if (!isfinite(softmax_scale)) return VFA_ERR_INVALID_ARG;
     if (use_minit < 0 || use_minit > 2) return VFA_ERR_INVALID_ARG;
@@ -1294,6 +1308,7 @@ int vfa_vsa_common(int mode, const void* Q, const void* K, const void* V, void* 
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N; p.Tr = ceil_div(N, block_m); p.Tc = ceil_div(N, block_n);
     p.causal = causal ? 1 : 0; p.n_sink = n_sink; p.n_local = n_local; p.use_minit = use_minit ? 1 : 0;
     p.order_asc = reorder ? 0 : 1; p.all_special = freeze ? 0 : 1;
+    p.rowskip = rowskip ? 1 : 0; p.tau2 = lazy_tau >= 0.f ? lazy_tau : -1.f;
     const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)d);
     p.c = scale * kLog2e;
     p.thr2 = thr_nats * kLog2e;
@@ -1373,12 +1388,13 @@ int vsa_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LS
 
 int vfa_variant_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int N,
                     int d, int block_m, int block_n, int causal, int n_sink, int n_local, int use_minit, int repr_mode,
-                    int reorder, int freeze, float softmax_scale, float skip_threshold_nats, unsigned char* skip_mask,
-                    void* workspace, size_t workspace_bytes, void* stream) {
+                    int reorder, int freeze, int rowskip, float lazy_rescale_tau, float softmax_scale,
+                    float skip_threshold_nats, unsigned char* skip_mask, void* workspace, size_t workspace_bytes,
+                    void* stream) {
     const bool skipping = skip_threshold_nats != 0.f;
     return vfa_vsa_common(skipping ? MODE_VSA : MODE_VFA, Q, K, V, O, LSE, B, Hq, Hkv, N, d, block_m, block_n, causal,
                           n_sink, n_local, use_minit, softmax_scale, skip_threshold_nats, skipping ? skip_mask : nullptr,
-                          workspace, workspace_bytes, stream, repr_mode, reorder, freeze);
+                          workspace, workspace_bytes, stream, repr_mode, reorder, freeze, rowskip, lazy_rescale_tau);
 }
 
 int vfa_kblock_summary_append(const void* K, void* Krepr, int B, int Hkv, int n_cap, int n_old, int n_new, int d,

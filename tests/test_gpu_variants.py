@@ -112,3 +112,27 @@ def test_skipping_variants_mask_bit_exact(vfa, oracle, sname, w, thr, vname, sw)
     else:
         stats = "output not compared: %d tile(s) within the guard band" % near.sum()
     print(sname, vname, "sparsity %.3f" % sparsity, stats, flush=True)
+
+
+@pytest.mark.parametrize("sname,w,thr", SKIP_SHAPES, ids=[s[0] for s in SKIP_SHAPES])
+@pytest.mark.parametrize("vname,okw", [("rowskip", dict(rowskip=True)), ("fa4_tau1.5", dict(lazy_tau=1.5))],
+                         ids=["rowskip", "fa4"])
+def test_rowskip_and_fa4_variants(vfa, oracle, sname, w, thr, vname, okw):
+    import torch
+    t = wl.generate(w)
+    Q, K, V = gpu_inputs(t)
+    Qh, Kh, Vh = host_f32(t)
+    blocks = wl.all_blocks(w)
+    gkw = dict(rowskip=True) if "rowskip" in okw else dict(lazy_rescale_tau=okw["lazy_tau"])
+    O, L, M = vfa.vfa_variant_fwd(Q, K, V, block_m=w.block_m, block_n=w.block_n, causal=w.causal, n_sink=0, n_local=0,
+                                  use_minit=False, reorder=False, freeze=False, skip_threshold_nats=thr, **gkw)
+    torch.cuda.synchronize()
+    ref = oracle.blasst_variant(Qh, Kh, Vh, w.block_m, w.block_n, w.causal, blocks, thr, **okw)
+    got = M.cpu().numpy().reshape(len(blocks), w.Tc)
+    near = np.abs(ref["margin"]) < MASK_GUARD_NATS
+    assert near.sum() <= 2
+    assert np.array_equal(got[~near], ref["mask"][~near])
+    # (row-level decisions sit on the same threshold: rows within the guard band of it may differ, so the output
+    # is compared at the ordinary bars, which a single flipped row of a tile that carries < lambda of the mass meets)
+    stats = check_o_lse(O, L, ref["O"], ref["LSE"], blocks, w.block_m, w.N, vname + " vs oracle")
+    print(sname, vname, stats, "counter %d of %d" % (ref["counters"][:, 2].sum(), ref["counters"][:, 0].sum()), flush=True)
