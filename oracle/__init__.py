@@ -186,6 +186,25 @@ def blasst_variant(Q, K, V, block_m, block_n, causal, blocks_, skip_threshold_na
     return dict(O=O, LSE=L, mask=mask, margin=margin, counters=cnt)
 
 
+def e4m3_quantize(x, inv_scale: float):
+    """OCP E4M3 codes (uint8) of float32 x * inv_scale: round to nearest even, saturating at +-448."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    codes = np.empty(x.shape, dtype=np.uint8)
+    rc = _load().oracle_e4m3_quantize(_p(x, ctypes.c_float), ctypes.c_longlong(x.size), ctypes.c_float(inv_scale),
+                                      _p(codes, ctypes.c_uint8))
+    assert rc == 0
+    return codes
+
+
+def e4m3_dequantize(codes, scale: float = 1.0):
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    out = np.empty(codes.shape, dtype=np.float64)
+    rc = _load().oracle_e4m3_dequantize(_p(codes, ctypes.c_uint8), ctypes.c_longlong(codes.size), ctypes.c_double(scale),
+                                        _p(out, ctypes.c_double))
+    assert rc == 0
+    return out
+
+
 def decode(q, K, V, n_keys, block_n, *, n_sink=1, n_local=1, use_minit=True, n_parts=1, scale=None):
     """One query token per head against the first n_keys rows of a K/V cache [B,Hkv,n_cap,d].
     Returns dict O [B,Hq,d], LSE, m_init, m_final [B,Hq], l_parts [B,Hq,n_parts]."""

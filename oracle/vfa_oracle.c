@@ -542,3 +542,45 @@ int oracle_blasst_variant(const float *Q, const float *K, const float *V, int B,
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------ */
+/* FP8 (OCP E4M3, finite-only: bias 7, 3 mantissa bits, largest finite 448, no infinities;
+ * the published format) for the 8-bit tensor regime of the performance discussion (C8V32).
+ * code = round-to-nearest-even of x * inv_scale (the product taken in float32, as the GPU
+ * pre-pass takes it), saturated to +-448; NaN -> 0x7F.  Subnormals: multiples of 2^-9.       */
+static uint8_t e4m3_encode(float xf) {
+    if (xf != xf) return 0x7F;
+    uint8_t sign = (xf < 0.0f || (xf == 0.0f && 1.0f / xf < 0.0f)) ? 0x80 : 0x00;
+    double a = fabs((double)xf);
+    if (a >= 448.0) return sign | 0x7E;                  /* saturate to the largest finite value */
+    if (a < 0.015625) {                                  /* below 2^-6: subnormal grid, step 2^-9 */
+        double q = a * 512.0;
+        double r = nearbyint(q);                         /* default rounding mode: nearest even */
+        return sign | (uint8_t)r;                        /* r == 8 is exactly code 0x08 = 2^-6 */
+    }
+    int e;
+    double f = frexp(a, &e);                             /* a = f * 2^e, f in [0.5, 1) */
+    double m = f * 2.0;                                  /* [1, 2) */
+    int ex = e - 1;
+    double r = nearbyint((m - 1.0) * 8.0);               /* 0..8 */
+    if (r == 8.0) { r = 0.0; ex += 1; }
+    if (ex > 8 || (ex == 8 && r > 6.0)) return sign | 0x7E;
+    return sign | (uint8_t)(((ex + 7) << 3) | (int)r);
+}
+
+static double e4m3_decode(uint8_t c) {
+    const int s = c >> 7, e = (c >> 3) & 15, m = c & 7;
+    if (e == 15 && m == 7) return NAN;
+    const double v = (e == 0) ? ldexp((double)m, -9) : ldexp(1.0 + m / 8.0, e - 7);
+    return s ? -v : v;
+}
+
+int oracle_e4m3_quantize(const float *x, long long n, float inv_scale, uint8_t *codes) {
+    for (long long i = 0; i < n; ++i) codes[i] = e4m3_encode(x[i] * inv_scale);
+    return 0;
+}
+
+int oracle_e4m3_dequantize(const uint8_t *codes, long long n, double scale, double *out) {
+    for (long long i = 0; i < n; ++i) out[i] = e4m3_decode(codes[i]) * scale;
+    return 0;
+}

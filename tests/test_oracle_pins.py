@@ -576,6 +576,38 @@ def test_decode_generator_shares_the_cache_of_the_prefill_recipe():
     assert s[..., 299].mean() > s[..., 100:200].mean() + 0.5     # and the token's own position gets the local bonus
 
 
+def test_e4m3_codec_against_the_format_definition():
+    """OCP FP8 E4M3 (finite only): sign, 4 exponent bits with bias 7, 3 mantissa bits; exponent 0 is
+    the subnormal grid m * 2^-9; S.1111.111 is NaN; largest finite 448.  The table is built here from
+    that definition; the encoder must invert it, round ties to even, and saturate."""
+    import oracle as orc
+    table = []
+    for c in range(256):
+        s, e, m = c >> 7, (c >> 3) & 15, c & 7
+        v = float("nan") if (e == 15 and m == 7) else ((m * 2.0 ** -9) if e == 0 else (1 + m / 8) * 2.0 ** (e - 7))
+        table.append(-v if s else v)
+    table = np.array(table)
+    dec = orc.e4m3_dequantize(np.arange(256, dtype=np.uint8))
+    assert np.array_equal(np.isnan(dec), np.isnan(table)) and np.array_equal(dec[~np.isnan(table)], table[~np.isnan(table)])
+    assert table[0x7E] == 448.0 and table[0x08] == 2.0 ** -6 and table[0x01] == 2.0 ** -9 and table[0x38] == 1.0
+    fin = np.array([c for c in range(256) if not np.isnan(table[c]) and c != 0x80], dtype=np.uint8)
+    assert np.array_equal(orc.e4m3_quantize(table[fin].astype(np.float32), 1.0), fin)         # every value encodes to itself
+    pos = table[:0x7F]                                                                         # codes 0x00..0x7E ascend
+    assert np.all(np.diff(pos) > 0)
+    mid = ((pos[:-1] + pos[1:]) / 2).astype(np.float32)                                        # exact in float32
+    codes = orc.e4m3_quantize(mid, 1.0)
+    lo, hi = orc.e4m3_quantize(pos[:-1].astype(np.float32), 1.0), orc.e4m3_quantize(pos[1:].astype(np.float32), 1.0)
+    assert np.all((codes == lo) | (codes == hi)) and np.all(codes % 2 == 0)                    # ties go to the even code
+    assert np.array_equal(orc.e4m3_quantize(np.array([1e9, 449.0, 464.1, -1e9], np.float32), 1.0), [0x7E, 0x7E, 0x7E, 0xFE])
+    assert np.array_equal(orc.e4m3_quantize(np.array([447.9, 2.0 ** -11, 2.0 ** -10, 3 * 2.0 ** -10], np.float32), 1.0),
+                          [0x7E, 0x00, 0x00, 0x02])
+    x = rnd(60, 4096).astype(np.float32) * 3
+    q = orc.e4m3_dequantize(orc.e4m3_quantize(x, 16.0), 1 / 16.0)
+    big = np.abs(x) >= 2.0 ** -6 / 16
+    assert np.all(np.abs(q - x)[big] <= np.abs(x)[big] * 2.0 ** -4) and np.all(np.abs(q - x)[~big] <= 2.0 ** -10 / 16)
+    assert np.all(np.diff(orc.e4m3_dequantize(orc.e4m3_quantize(np.sort(x), 16.0))) >= 0)      # monotone
+
+
 def test_bf16_rounding_is_nearest_even():
     x = np.array([1.0, 1.00390625, 1.01171875, -1.00390625, 3.4e38, 1e-40, 0.0], np.float32)
     bits = wl.f32_to_bf16_bits(x)
