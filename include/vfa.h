@@ -165,6 +165,36 @@ int vfa_decode_fwd(const void* Q, const void* K, const void* V, const void* Krep
                    int n_sink, int n_local, int use_minit, int n_splits, float softmax_scale,
                    void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- FP8 (E4M3) path: the 8-bit tensor regime of the paper's performance discussion ("C8V32":
+ * both matrix products in 8 bit, softmax arithmetic in fp32).  The paper gives no quantisation
+ * scheme; this one is per-tensor: x8 = E4M3(x * inv_scale), round to nearest even, saturated at
+ * +-448, and the attention call receives the matching descale factors (1 / inv_scale).
+ * Only d = 128 with 128x64 blocks. ---- */
+
+/* X (bf16, n elements, n a multiple of 8, 16-byte aligned) -> X8 (n E4M3 codes, same order). */
+int vfa_fp8_quantize(const void* X, void* X8, long long n, float inv_scale, void* stream);
+
+/* V [B, Hkv, N, 128] bf16 -> Vt8 [B, Hkv, ceil(N/64), 128, 64] E4M3: per 64-key tile a block of 128
+ * feature rows by 64 keys, the keys in the order the P.V operand wants them (byte 32 h + j of a row
+ * is key 32 (j/16) + 8 ((j%16)/4) + 4 h + j%4 of the tile); keys beyond N are written as zero.
+ * vfa_fp8_v_bytes gives the size of Vt8. */
+size_t vfa_fp8_v_bytes(int B, int Hkv, int N);
+int vfa_fp8_pack_v(const void* V, void* Vt8, int B, int Hkv, int N, int d, float inv_scale, void* stream);
+
+/* Attention forward on E4M3 operands.  frozen = 0: online softmax on every block (the FA column of
+ * Table 1); frozen = 1: Alg. 1 (summaries are the sabsmax of the K codes, an element of K8 again;
+ * n_sink, n_local, use_minit as in vfa_attn_fwd, with workspace >= B * Hkv * ceil(N/64) * 128 bytes).
+ * Scores are (code products) * descale_q * descale_k * softmax_scale; exp(S - m) is rounded to E4M3
+ * scaled by 2^8 (frozen = 0) or 2^4 (frozen = 1, leaving 4 binades for scores above the frozen max;
+ * beyond them exp is capped, never NaN); l sums the unrounded values; O = descale_v * (P8 V8) / l is
+ * written in bf16 and LSE in fp32 as in the bf16 entry points.  Q8, K8 [B, H, N, 128] codes.
+ * Errors as vfa_attn_fwd; VFA_ERR_UNSUPPORTED unless d = 128, block_m = 128, block_n = 64. */
+int vfa_fp8_attn_fwd(int frozen, const void* Q8, const void* K8, const void* Vt8, void* O, float* LSE,
+                     int B, int Hq, int Hkv, int N, int d, int block_m, int block_n, int causal,
+                     int n_sink, int n_local, int use_minit, float softmax_scale, float descale_q,
+                     float descale_k, float descale_v, void* workspace, size_t workspace_bytes,
+                     void* stream);
+
 /* Static string for a return code. */
 const char* vfa_strerror(int code);
 

@@ -15,7 +15,8 @@ _lib = None
 
 EXPORTS = ("vfa_workspace_bytes", "vfa_kblock_summary", "vfa_kblock_summary_mode", "fa_baseline_fwd",
            "fa_lazy_rescale_fwd", "vfa_attn_fwd", "vsa_attn_fwd", "vfa_variant_fwd", "vfa_kblock_summary_append",
-           "vfa_decode_workspace_bytes", "vfa_decode_fwd", "vfa_strerror")
+           "vfa_decode_workspace_bytes", "vfa_decode_fwd", "vfa_fp8_quantize", "vfa_fp8_v_bytes", "vfa_fp8_pack_v",
+           "vfa_fp8_attn_fwd", "vfa_strerror")
 
 
 class VfaError(RuntimeError):
@@ -46,6 +47,14 @@ def lib() -> ctypes.CDLL:
         L.vfa_decode_workspace_bytes.argtypes = [i, i, i, i]
         L.vfa_decode_fwd.restype = i
         L.vfa_decode_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, i, i, f, vp, sz, vp]
+        L.vfa_fp8_quantize.restype = i
+        L.vfa_fp8_quantize.argtypes = [vp, vp, ctypes.c_longlong, f, vp]
+        L.vfa_fp8_v_bytes.restype = sz
+        L.vfa_fp8_v_bytes.argtypes = [i, i, i]
+        L.vfa_fp8_pack_v.restype = i
+        L.vfa_fp8_pack_v.argtypes = [vp, vp, i, i, i, i, f, vp]
+        L.vfa_fp8_attn_fwd.restype = i
+        L.vfa_fp8_attn_fwd.argtypes = [i, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, i, i, f, f, f, f, vp, sz, vp]
         L.fa_baseline_fwd.restype = i
         L.fa_baseline_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, f, vp]
         L.fa_lazy_rescale_fwd.restype = i
@@ -231,4 +240,45 @@ def decode_fwd(q, K, V, n_keys: int, *, krepr=None, block_n=64, n_sink=1, n_loca
                               _ptr(ws), ws.numel() * ws.element_size(), _stream(stream))
     if rc != 0:
         raise VfaError(rc, "vfa_decode_fwd")
+    return O, L
+
+
+def fp8_quantize(X, inv_scale: float, stream=None):
+    """bf16 tensor -> uint8 tensor of E4M3 codes of X * inv_scale (same shape)."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.bfloat16 and X.is_contiguous()
+    Y = torch.empty(X.shape, dtype=torch.uint8, device=X.device)
+    rc = lib().vfa_fp8_quantize(_ptr(X), _ptr(Y), X.numel(), float(inv_scale), _stream(stream))
+    if rc != 0:
+        raise VfaError(rc, "vfa_fp8_quantize")
+    return Y
+
+
+def fp8_pack_v(V, inv_scale: float, stream=None):
+    """V [B, Hkv, N, 128] bf16 -> [B, Hkv, ceil(N/64), 128, 64] uint8 (transposed, key-permuted E4M3 tiles)."""
+    import torch
+    B, Hkv, N, d = V.shape
+    Vt = torch.empty((B, Hkv, -(-N // 64), 128, 64), dtype=torch.uint8, device=V.device)
+    rc = lib().vfa_fp8_pack_v(_ptr(V), _ptr(Vt), B, Hkv, N, d, float(inv_scale), _stream(stream))
+    if rc != 0:
+        raise VfaError(rc, "vfa_fp8_pack_v")
+    return Vt
+
+
+def fp8_attn_fwd(Q8, K8, Vt8, *, descale_q, descale_k, descale_v, frozen=True, block_m=128, block_n=64, causal=True,
+                 n_sink=1, n_local=1, use_minit=True, softmax_scale=0.0, workspace=None, out=None, lse=None,
+                 want_lse=True, stream=None):
+    import torch
+    B, Hq, N, d = Q8.shape
+    Hkv = K8.shape[1]
+    O = torch.empty((B, Hq, N, d), dtype=torch.bfloat16, device=Q8.device) if out is None else out
+    L = lse if (lse is not None or not want_lse) else torch.empty((B, Hq, N), dtype=torch.float32, device=Q8.device)
+    need = B * Hkv * (-(-N // block_n)) * 128
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=Q8.device) if workspace is None else workspace
+    rc = lib().vfa_fp8_attn_fwd(int(bool(frozen)), _ptr(Q8), _ptr(K8), _ptr(Vt8), _ptr(O), _ptr(L), B, Hq, Hkv, N, d, block_m,
+                                block_n, int(bool(causal)), int(n_sink), int(n_local), int(use_minit), float(softmax_scale),
+                                float(descale_q), float(descale_k), float(descale_v), _ptr(ws),
+                                ws.numel() * ws.element_size(), _stream(stream))
+    if rc != 0:
+        raise VfaError(rc, "vfa_fp8_attn_fwd")
     return O, L

@@ -94,6 +94,21 @@ def test_bad_arguments_are_rejected_before_launch(pkg):
     assert dc(p, p, p, p, p, none, *dshape, 100, 128, 32, 1, 1, 1, 4, 0.0, p, 1 << 20, none) == -2   # block_n
     assert dc(p, p, p, p, p, none, 0, 8, 2, 1024, 100, 128, 64, 1, 1, 1, 4, 0.0, p, 1 << 20, none) == 0
     assert pkg.decode_workspace_bytes(1, 8, 128, 4) >= 1 * 8 * 4 * 130 * 4
+    f8 = lambda *a: L.vfa_fp8_attn_fwd(*a)
+    f8shape = (1, 4, 2, 256, 128, 128, 64, 1)
+    assert f8(1, p, p, p, p, none, *f8shape, 1, 1, 1, 0.0, 1.0, 1.0, 1.0, none, 0, none) == -1        # summaries need a workspace
+    assert f8(1, p, p, p, p, none, *f8shape, 1, 1, 1, 0.0, 0.0, 1.0, 1.0, p, 1 << 20, none) == -1      # descale must be > 0
+    assert f8(2, p, p, p, p, none, *f8shape, 1, 1, 1, 0.0, 1.0, 1.0, 1.0, p, 1 << 20, none) == -1      # frozen is 0 or 1
+    assert f8(1, p, p, p, p, none, *f8shape, 0, 0, 0, 0.0, 1.0, 1.0, 1.0, p, 1 << 20, none) == -1      # max would stay -inf
+    assert f8(0, p, p, p, p, none, 1, 4, 2, 256, 64, 128, 64, 1, 1, 1, 1, 0.0, 1.0, 1.0, 1.0, p, 1 << 20, none) == -2   # d = 64
+    assert f8(0, none, p, p, p, none, *f8shape, 1, 1, 1, 0.0, 1.0, 1.0, 1.0, p, 1 << 20, none) == -1
+    assert f8(0, p, p, p, p, none, 0, 4, 2, 256, 128, 128, 64, 1, 1, 1, 1, 0.0, 1.0, 1.0, 1.0, none, 0, none) == 0
+    assert L.vfa_fp8_quantize(p, p, 12, 1.0, none) == -1                                              # not a multiple of 8
+    assert L.vfa_fp8_quantize(p, p, 16, -1.0, none) == -1
+    assert L.vfa_fp8_quantize(p, p, 0, 1.0, none) == 0
+    assert L.vfa_fp8_pack_v(p, p, 1, 1, 64, 64, 1.0, none) == -2
+    assert L.vfa_fp8_pack_v(none, p, 1, 1, 64, 128, 1.0, none) == -1
+    assert L.vfa_fp8_v_bytes(2, 4, 100) == 2 * 4 * 2 * 8192
     assert L.vfa_kblock_summary_mode(p, p, 1, 1, 64, 128, 64, 7, none) == -1
     assert L.vfa_kblock_summary_mode(none, p, 1, 1, 64, 128, 64, 2, none) == -1
     assert L.vfa_kblock_summary(none, p, 1, 1, 64, 128, 64, none) == -1
