@@ -165,6 +165,20 @@ int vfa_decode_fwd(const void* Q, const void* K, const void* V, const void* Krep
                    int n_sink, int n_local, int use_minit, int n_splits, float softmax_scale,
                    void* workspace, size_t workspace_bytes, void* stream);
 
+/* The two decode calls for a batch whose sequences have different lengths.  old_lens / new_lens /
+ * seq_lens are DEVICE arrays of B ints (4-byte aligned), read by the kernels (the host never looks at
+ * them, so a serving loop can update them on the GPU): sequence b has seq_lens[b] valid rows in its
+ * part of the cache, values are clamped to [1, n_cap] (to [0, n_cap] in the append call, where
+ * old >= new means nothing to do).  Everything else as in vfa_kblock_summary_append / vfa_decode_fwd;
+ * each sequence's key range is cut into n_splits ranges of its own length. */
+int vfa_kblock_summary_append_varlen(const void* K, void* Krepr, int B, int Hkv, int n_cap,
+                                     const int* old_lens, const int* new_lens, int d, int block_n,
+                                     void* stream);
+int vfa_decode_varlen_fwd(const void* Q, const void* K, const void* V, const void* Krepr, void* O,
+                          float* LSE, int B, int Hq, int Hkv, int n_cap, const int* seq_lens, int d,
+                          int block_n, int n_sink, int n_local, int use_minit, int n_splits,
+                          float softmax_scale, void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- FP8 (E4M3) path: the 8-bit tensor regime of the paper's performance discussion ("C8V32":
  * both matrix products in 8 bit, softmax arithmetic in fp32).  The paper gives no quantisation
  * scheme; this one is per-tensor: x8 = E4M3(x * inv_scale), round to nearest even, saturated at

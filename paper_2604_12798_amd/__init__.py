@@ -15,7 +15,7 @@ _lib = None
 
 EXPORTS = ("vfa_workspace_bytes", "vfa_kblock_summary", "vfa_kblock_summary_mode", "fa_baseline_fwd",
            "fa_lazy_rescale_fwd", "vfa_attn_fwd", "vsa_attn_fwd", "vfa_variant_fwd", "vfa_kblock_summary_append",
-           "vfa_decode_workspace_bytes", "vfa_decode_fwd", "vfa_fp8_quantize", "vfa_fp8_v_bytes", "vfa_fp8_pack_v",
+           "vfa_decode_workspace_bytes", "vfa_decode_fwd", "vfa_kblock_summary_append_varlen", "vfa_decode_varlen_fwd", "vfa_fp8_quantize", "vfa_fp8_v_bytes", "vfa_fp8_pack_v",
            "vfa_fp8_attn_fwd", "vfa_strerror")
 
 
@@ -47,6 +47,10 @@ def lib() -> ctypes.CDLL:
         L.vfa_decode_workspace_bytes.argtypes = [i, i, i, i]
         L.vfa_decode_fwd.restype = i
         L.vfa_decode_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, i, i, f, vp, sz, vp]
+        L.vfa_kblock_summary_append_varlen.restype = i
+        L.vfa_kblock_summary_append_varlen.argtypes = [vp, vp, i, i, i, vp, vp, i, i, vp]
+        L.vfa_decode_varlen_fwd.restype = i
+        L.vfa_decode_varlen_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp, i, i, i, i, i, i, f, vp, sz, vp]
         L.vfa_fp8_quantize.restype = i
         L.vfa_fp8_quantize.argtypes = [vp, vp, ctypes.c_longlong, f, vp]
         L.vfa_fp8_v_bytes.restype = sz
@@ -216,6 +220,36 @@ def kblock_summary_append(K, Krepr, n_old: int, n_new: int, block_n: int = 64, s
     if rc != 0:
         raise VfaError(rc, "vfa_kblock_summary_append")
     return Krepr
+
+
+def kblock_summary_append_varlen(K, Krepr, old_lens, new_lens, block_n: int = 64, stream=None):
+    """As kblock_summary_append with per-sequence lengths (int32 device tensors of B entries)."""
+    B, Hkv, n_cap, d = K.shape
+    rc = lib().vfa_kblock_summary_append_varlen(_ptr(K), _ptr(Krepr), B, Hkv, n_cap, _ptr(old_lens), _ptr(new_lens), d,
+                                                block_n, _stream(stream))
+    if rc != 0:
+        raise VfaError(rc, "vfa_kblock_summary_append_varlen")
+    return Krepr
+
+
+def decode_varlen_fwd(q, K, V, seq_lens, *, krepr=None, block_n=64, n_sink=1, n_local=1, use_minit=True, n_splits=8,
+                      softmax_scale=0.0, workspace=None, out=None, lse=None, want_lse=True, stream=None):
+    """As decode_fwd with per-sequence lengths (int32 device tensor of B entries)."""
+    import torch
+    B, Hq, d = q.shape
+    Hkv, n_cap = K.shape[1], K.shape[2]
+    assert seq_lens.is_cuda and seq_lens.dtype == torch.int32 and seq_lens.numel() == B
+    O = torch.empty_like(q) if out is None else out
+    L = lse if (lse is not None or not want_lse) else torch.empty((B, Hq), dtype=torch.float32, device=q.device)
+    need = decode_workspace_bytes(B, Hq, d, n_splits)
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device) if workspace is None else workspace
+    rc = lib().vfa_decode_varlen_fwd(_ptr(q), _ptr(K), _ptr(V), _ptr(krepr), _ptr(O), _ptr(L), B, Hq, Hkv, n_cap,
+                                     _ptr(seq_lens), d, block_n, int(n_sink), int(n_local), int(bool(use_minit)),
+                                     int(n_splits), float(softmax_scale), _ptr(ws), ws.numel() * ws.element_size(),
+                                     _stream(stream))
+    if rc != 0:
+        raise VfaError(rc, "vfa_decode_varlen_fwd")
+    return O, L
 
 
 def decode_workspace_bytes(B: int, Hq: int, d: int, n_splits: int) -> int:

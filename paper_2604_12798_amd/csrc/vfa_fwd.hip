@@ -985,13 +985,23 @@ __device__ inline uint32_t sabs_pick2(uint32_t a, uint32_t b) {  // two packed b
 // N = row stride of one head's key array (its capacity), n_valid = keys present, Tc = block stride of
 // one head's summary array, j0 = first block to (re)compute: a growing cache recomputes only the
 // blocks that received keys.
+// With per-sequence lengths (old_len / new_len device arrays indexed by batch entry, Hkv heads per entry) the
+// grid covers every block of the capacity and a workgroup whose block received no key returns at once.
 template <int D>
 __global__ __launch_bounds__(256) void kblock_summary_kernel(const uint16_t* __restrict__ K, uint16_t* __restrict__ R,
-                                                             int N, int n_valid, int Tc, int block_n, int j0) {
+                                                             int N, int n_valid, int Tc, int block_n, int j0,
+                                                             const int* __restrict__ old_len = nullptr,
+                                                             const int* __restrict__ new_len = nullptr, int Hkv = 1) {
     constexpr int CH = D / 8;        // 16-byte chunks per row
     constexpr int RG = 256 / CH;     // row groups
     __shared__ u32x4 part[RG][CH];
     const int j = j0 + blockIdx.x, bh = blockIdx.y;
+    if (new_len) {
+        const int b = bh / Hkv;
+        const int n_new = min(max(new_len[b], 0), N), n_old = min(max(old_len[b], 0), n_new);
+        if (j < n_old / block_n || j * block_n >= n_new) return;  // (uniform over the workgroup)
+        n_valid = n_new;
+    }
     const int ch = threadIdx.x % CH, rg = threadIdx.x / CH;
     const int c0 = j * block_n, c1 = min(n_valid, c0 + block_n);
     const uint16_t* base = K + (size_t)bh * N * D;
@@ -1081,6 +1091,7 @@ struct DecodeParams {
     uint16_t* O;            // [B, Hq, d]
     float* LSE;             // [B, Hq] or null
     int B, Hq, Hkv, n_cap, n_keys, tc_cap, n_splits, n_sink, n_local, use_minit;
+    const int* seq_lens;    // null, or [B] device array: valid keys per batch entry (clamped to [1, n_cap]) instead of n_keys
     float c;
 };
 
@@ -1103,7 +1114,8 @@ __global__ __launch_bounds__(64) void decode_max_kernel(const DecodeParams p) {
     int b, h;
     bf16x8 qf[D / 16];
     decode_rows<D>(p, bh, lane, b, h, qf);
-    const int Tc = (p.n_keys + BN - 1) / BN;
+    const int n_keys = p.seq_lens ? min(max(p.seq_lens[b], 1), p.n_cap) : p.n_keys;
+    const int Tc = (n_keys + BN - 1) / BN;
     float mx = -INFINITY;
     f32x16 st[2];
     if (p.use_minit) {
@@ -1121,10 +1133,10 @@ __global__ __launch_bounds__(64) void decode_max_kernel(const DecodeParams p) {
     const uint16_t* Kg = p.K + (size_t)bh * p.n_cap * D;
     for (int u = split; u < n1 + (Tc - lo2); u += p.n_splits) {
         const int j = u < n1 ? u : lo2 + (u - n1);
-        load_tile<D, 1>(Kg, j * BN, p.n_keys, buf, false, 0, lane);
+        load_tile<D, 1>(Kg, j * BN, n_keys, buf, false, 0, lane);
         wait_vm0_and_sync();
         qk_tile_pipe<D>(buf, qf, st, ql, hh);
-        mx = fmaxf(mx, tile_rowmax<true>(st, j * BN, p.n_keys - 1, hh));
+        mx = fmaxf(mx, tile_rowmax<true>(st, j * BN, n_keys - 1, hh));
         __syncthreads();
     }
     const float m2 = xhalf_max(mx) * p.c;
@@ -1151,7 +1163,8 @@ __global__ __launch_bounds__(64) void decode_split_kernel(const DecodeParams p) 
     float m2 = -INFINITY;
     for (int s = 0; s < p.n_splits; ++s) m2 = fmaxf(m2, p.pm[row * p.n_splits + s]);
 
-    const int Tc = (p.n_keys + BN - 1) / BN;
+    const int n_keys = p.seq_lens ? min(max(p.seq_lens[b], 1), p.n_cap) : p.n_keys;
+    const int Tc = (n_keys + BN - 1) / BN;
     const int per = (Tc + p.n_splits - 1) / p.n_splits;
     const int t_lo = split * per, t_hi = min(Tc, t_lo + per);
     const uint16_t* Kg = p.K + (size_t)bh * p.n_cap * D;
@@ -1161,19 +1174,19 @@ __global__ __launch_bounds__(64) void decode_split_kernel(const DecodeParams p) 
     for (int db = 0; db < DB; ++db) ot[db] = f32x16{0};
     float lsum = 0.f;
     if (t_lo < t_hi) {
-        load_tile<D, 1>(Kg, t_lo * BN, p.n_keys, Ks, false, 0, lane);
+        load_tile<D, 1>(Kg, t_lo * BN, n_keys, Ks, false, 0, lane);
         wait_vm0_and_sync();
     }
     for (int t = t_lo; t < t_hi; ++t) {
         const int cur = (t - t_lo) & 1;
         // the V buffer's last readers (the P.V MFMAs of the previous tile) have all issued
-        load_tile<D, 1>(Vg, t * BN, p.n_keys, Vs, true, 0, lane);
+        load_tile<D, 1>(Vg, t * BN, n_keys, Vs, true, 0, lane);
         const bool more = t + 1 < t_hi;
-        if (more) load_tile<D, 1>(Kg, (t + 1) * BN, p.n_keys, Ks + (cur ^ 1) * T::BYTES, false, 0, lane);
+        if (more) load_tile<D, 1>(Kg, (t + 1) * BN, n_keys, Ks + (cur ^ 1) * T::BYTES, false, 0, lane);
         f32x16 st[2];
         uint32_t pk[16];
         qk_tile_pipe<D>(Ks + cur * T::BYTES, qf, st, ql, hh);
-        softmax_tile<false, true, DB>(st, pk, ot, m2, lsum, p.c, t * BN, p.n_keys - 1, hh);  // frozen max, ragged tail masked
+        softmax_tile<false, true, DB>(st, pk, ot, m2, lsum, p.c, t * BN, n_keys - 1, hh);  // frozen max, ragged tail masked
         if (more) __builtin_amdgcn_s_waitcnt(WAIT_ALL_BUT_ONE_TILE);  // V(t) has landed; K(t + 1) may still be on its way
         else __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
@@ -1684,6 +1697,10 @@ int fa_common(bool lazy, const void* Q, const void* K, const void* V, void* O, f
                 : launch_fwd<MODE_FA>(p, d, block_m, (hipStream_t)stream);
 }
 
+int decode_common(const void* Q, const void* K, const void* V, const void* Krepr, void* O, float* LSE, int B, int Hq,
+                  int Hkv, int n_cap, int n_keys, const int* seq_lens, int d, int block_n, int n_sink, int n_local,
+                  int use_minit, int n_splits, float softmax_scale, void* workspace, size_t workspace_bytes, void* stream);
+
 }  // namespace
 
 extern "C" {
@@ -1777,9 +1794,47 @@ size_t vfa_decode_workspace_bytes(int B, int Hq, int d, int n_splits) {
 int vfa_decode_fwd(const void* Q, const void* K, const void* V, const void* Krepr, void* O, float* LSE, int B, int Hq,
                    int Hkv, int n_cap, int n_keys, int d, int block_n, int n_sink, int n_local, int use_minit,
                    int n_splits, float softmax_scale, void* workspace, size_t workspace_bytes, void* stream) {
+    if (n_keys < 1 || n_keys > n_cap) return VFA_ERR_INVALID_ARG;
+    return decode_common(Q, K, V, Krepr, O, LSE, B, Hq, Hkv, n_cap, n_keys, nullptr, d, block_n, n_sink, n_local, use_minit,
+                         n_splits, softmax_scale, workspace, workspace_bytes, stream);
+}
+
+int vfa_decode_varlen_fwd(const void* Q, const void* K, const void* V, const void* Krepr, void* O, float* LSE, int B,
+                          int Hq, int Hkv, int n_cap, const int* seq_lens, int d, int block_n, int n_sink, int n_local,
+                          int use_minit, int n_splits, float softmax_scale, void* workspace, size_t workspace_bytes,
+                          void* stream) {
+    if (B > 0 && (!seq_lens || (reinterpret_cast<uintptr_t>(seq_lens) & 3u))) return VFA_ERR_INVALID_ARG;
+    return decode_common(Q, K, V, Krepr, O, LSE, B, Hq, Hkv, n_cap, n_cap, seq_lens, d, block_n, n_sink, n_local, use_minit,
+                         n_splits, softmax_scale, workspace, workspace_bytes, stream);
+}
+
+int vfa_kblock_summary_append_varlen(const void* K, void* Krepr, int B, int Hkv, int n_cap, const int* old_lens,
+                                     const int* new_lens, int d, int block_n, void* stream) {
+    if (B < 0 || Hkv <= 0 || n_cap < 0 || block_n <= 0) return VFA_ERR_INVALID_ARG;
+    if (d != 64 && d != 128) return VFA_ERR_UNSUPPORTED;
+    if (B == 0 || n_cap == 0) return VFA_OK;
+    if (!K || !Krepr || !old_lens || !new_lens || !aligned16(K) || !aligned16(Krepr)) return VFA_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(old_lens) | reinterpret_cast<uintptr_t>(new_lens)) & 3u) return VFA_ERR_INVALID_ARG;
+    if ((long long)B * Hkv > 65535) return VFA_ERR_UNSUPPORTED;
+    const int tc_cap = ceil_div(n_cap, block_n);
+    const dim3 grid((unsigned)tc_cap, (unsigned)(B * Hkv));
+    hipStream_t s = (hipStream_t)stream;
+    (void)hipGetLastError();
+    if (d == 128)
+        kblock_summary_kernel<128><<<grid, 256, 0, s>>>((const uint16_t*)K, (uint16_t*)Krepr, n_cap, 0, tc_cap, block_n, 0, old_lens, new_lens, Hkv);
+    else
+        kblock_summary_kernel<64><<<grid, 256, 0, s>>>((const uint16_t*)K, (uint16_t*)Krepr, n_cap, 0, tc_cap, block_n, 0, old_lens, new_lens, Hkv);
+    return hipGetLastError() == hipSuccess ? VFA_OK : VFA_ERR_HIP;
+}
+
+}  // extern "C"
+
+namespace {
+int decode_common(const void* Q, const void* K, const void* V, const void* Krepr, void* O, float* LSE, int B, int Hq,
+                  int Hkv, int n_cap, int n_keys, const int* seq_lens, int d, int block_n, int n_sink, int n_local,
+                  int use_minit, int n_splits, float softmax_scale, void* workspace, size_t workspace_bytes, void* stream) {
     if (B < 0 || Hq <= 0 || Hkv <= 0 || n_cap <= 0 || d <= 0 || block_n <= 0) return VFA_ERR_INVALID_ARG;
     if (Hq % Hkv != 0 || n_sink < 0 || n_local < 0 || n_splits < 1 || n_splits > 4096) return VFA_ERR_INVALID_ARG;
-    if (n_keys < 1 || n_keys > n_cap) return VFA_ERR_INVALID_ARG;
     if (use_minit != 0 && use_minit != 1) return VFA_ERR_INVALID_ARG;
     if (!use_minit && n_sink + n_local == 0) return VFA_ERR_INVALID_ARG;
     if (!isfinite(softmax_scale)) return VFA_ERR_INVALID_ARG;
@@ -1795,7 +1850,7 @@ int vfa_decode_fwd(const void* Q, const void* K, const void* V, const void* Krep
     DecodeParams p{};
     p.Q = (const uint16_t*)Q; p.K = (const uint16_t*)K; p.V = (const uint16_t*)V; p.Krepr = (const uint16_t*)Krepr;
     p.O = (uint16_t*)O; p.LSE = LSE;
-    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.n_cap = n_cap; p.n_keys = n_keys; p.tc_cap = ceil_div(n_cap, block_n);
+    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.n_cap = n_cap; p.n_keys = n_keys; p.seq_lens = seq_lens; p.tc_cap = ceil_div(n_cap, block_n);
     p.n_splits = n_splits; p.n_sink = n_sink; p.n_local = n_local; p.use_minit = use_minit;
     const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)d);
     p.c = scale * kLog2e;
@@ -1815,6 +1870,9 @@ int vfa_decode_fwd(const void* Q, const void* K, const void* V, const void* Krep
     }
     return hipGetLastError() == hipSuccess ? VFA_OK : VFA_ERR_HIP;
 }
+}  // namespace
+
+extern "C" {
 
 size_t vfa_fp8_v_bytes(int B, int Hkv, int N) {
     if (B <= 0 || Hkv <= 0 || N <= 0) return 0;

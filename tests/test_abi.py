@@ -93,6 +93,12 @@ def test_bad_arguments_are_rejected_before_launch(pkg):
     assert dc(p, p, p, p, p, none, 1, 64, 1, 1024, 100, 128, 64, 1, 1, 1, 4, 0.0, p, 1 << 22, none) == -2  # 64 heads per KV head
     assert dc(p, p, p, p, p, none, *dshape, 100, 128, 32, 1, 1, 1, 4, 0.0, p, 1 << 20, none) == -2   # block_n
     assert dc(p, p, p, p, p, none, 0, 8, 2, 1024, 100, 128, 64, 1, 1, 1, 4, 0.0, p, 1 << 20, none) == 0
+    dv = lambda *a: L.vfa_decode_varlen_fwd(*a)
+    assert dv(p, p, p, p, p, none, *dshape, none, 128, 64, 1, 1, 1, 4, 0.0, p, 1 << 20, none) == -1   # lengths missing
+    assert dv(p, p, p, p, p, none, *dshape, ctypes.c_void_p(0x1002), 128, 64, 1, 1, 1, 4, 0.0, p, 1 << 20, none) == -1
+    assert dv(p, p, p, p, p, none, 0, 8, 2, 1024, none, 128, 64, 1, 1, 1, 4, 0.0, p, 1 << 20, none) == 0
+    assert L.vfa_kblock_summary_append_varlen(p, p, 1, 1, 256, none, p, 128, 64, none) == -1
+    assert L.vfa_kblock_summary_append_varlen(p, p, 0, 1, 256, none, none, 128, 64, none) == 0
     assert pkg.decode_workspace_bytes(1, 8, 128, 4) >= 1 * 8 * 4 * 130 * 4
     f8 = lambda *a: L.vfa_fp8_attn_fwd(*a)
     f8shape = (1, 4, 2, 256, 128, 128, 64, 1)

@@ -128,3 +128,32 @@ def test_decode_full_size_in_bench_configuration(vfa, oracle):
           "fixed max minus m_init (nats): max %.2f" % float((ref["m_final"] - ref["m_init"]).max()), flush=True)
     assert np.isfinite(gap).all()
     assert err.max() <= O_MAX_ABS and err.mean() <= O_MEAN_ABS and lerr <= LSE_ABS
+
+
+def test_decode_with_per_sequence_lengths(vfa, oracle):
+    """A batch of four sequences of different lengths: summaries appended per sequence, one decode call;
+    every sequence must equal the single-sequence oracle at its own length."""
+    import torch
+    B, Hq, Hkv, n_cap, d = 4, 8, 2, 1024, 128
+    t = _cache(B=B, Hq=Hq, Hkv=Hkv, n_cap=n_cap, d=d)
+    K, V = to_gpu(t["K"]), to_gpu(t["V"])
+    Kh, Vh = wl.bf16_bits_to_f32(t["K"]), wl.bf16_bits_to_f32(t["V"])
+    lens = np.array([1, 777, 1024, 130], np.int32)
+    R = torch.full((B, Hkv, n_cap // 64, d), 3.0, dtype=torch.bfloat16, device="cuda")
+    half = torch.from_numpy(lens // 2).cuda()
+    full = torch.from_numpy(lens).cuda()
+    vfa.kblock_summary_append_varlen(K, R, torch.zeros(B, dtype=torch.int32, device="cuda"), half)
+    vfa.kblock_summary_append_varlen(K, R, half, full)                  # grow each sequence to its length
+    Qb = np.stack([t["Q"][b, :, lens[b] - 1] for b in range(B)])         # [B, Hq, d]: each sequence's newest token
+    O, L = vfa.decode_varlen_fwd(to_gpu(np.ascontiguousarray(Qb)), K, V, full, krepr=R, n_splits=5)
+    torch.cuda.synchronize()
+    got_R = R.float().cpu().numpy().astype(np.float64)
+    for b in range(B):
+        n = int(lens[b])
+        Tc = -(-n // 64)
+        assert np.array_equal(got_R[b, :, :Tc], oracle.sabsmax(Kh[b:b + 1, :, :n], 64)[0])
+        assert (got_R[b, :, Tc:] == 3.0).all()
+        ref = oracle.decode(wl.bf16_bits_to_f32(Qb[b:b + 1]), Kh[b:b + 1], Vh[b:b + 1], n, 64)
+        err = np.abs(O[b].float().cpu().numpy().astype(np.float64) - ref["O"][0])
+        lerr = np.abs(L[b].cpu().numpy().astype(np.float64) - ref["LSE"][0]).max()
+        assert err.max() <= O_MAX_ABS and err.mean() <= O_MEAN_ABS and lerr <= LSE_ABS, (b, n, err.max(), lerr)
