@@ -107,7 +107,7 @@ def main():
     ap.add_argument("--workload", default="cfg3", choices=sorted(wl.CONFIGS))
     ap.add_argument("--seed", type=int, default=wl.DEFAULT_SEED)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample", type=int, default=1500, help="random query blocks in the oracle timing sample")
+    ap.add_argument("--cpu-sample", type=int, default=3500, help="random query blocks in the oracle timing sample")
     ap.add_argument("--only", default="", help="comma list of fa,vfa,vsa,summary,decode,fp8 to time (default all)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
