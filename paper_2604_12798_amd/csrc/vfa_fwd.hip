@@ -633,27 +633,6 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
         qf[kk] = *reinterpret_cast<const bf16x8*>(Qg + (size_t)qrow_c * D + 16 * kk + 8 * hh);
 
     float m2 = -INFINITY;
-    if (!is_fa(MODE) && p.use_minit) {
-        const uint16_t* Rg = p.Krepr + ((size_t)(b * p.Hkv + hkv) * p.Tc) * D;
-        float mx = -INFINITY;
-        const int n_sum_tiles = (j_hi + BN) / BN;
-        // the whole K/V ring is free here: fetch up to 8 summary tiles (512 key blocks) at once, so the
-        // load latency is paid once per batch instead of once per tile
-        for (int t0 = 0; t0 < n_sum_tiles; t0 += 2 * PP_STAGES) {
-            const int nb = min(2 * PP_STAGES, n_sum_tiles - t0);
-            if (t0) __syncthreads();  // the previous batch's readers are done
-            for (int u = 0; u < nb; ++u)
-                load_tile<D, NWV>(Rg, (t0 + u) * BN, p.Tc, pp_smem + u * T::BYTES, false, wave, lane);
-            wait_vm0_and_sync();
-            for (int u = 0; u < nb; ++u) {
-                f32x16 st[2];
-                qk_tile<D>(pp_smem + u * T::BYTES, qf, st, ql, hh);
-                mx = fmaxf(mx, tile_rowmax<true>(st, (t0 + u) * BN, j_hi_g, hh));
-            }
-        }
-        m2 = xhalf_max(mx) * p.c;
-        __syncthreads();
-    }
 
     Visit vis = make_visit<MODE>(p, a_lo, a_hi, j_hi);
     if (MODE == MODE_VSA && pb) {
@@ -867,9 +846,30 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
     using std::false_type;
     using std::true_type;
 
-    // ---- prologue: visits 0 and 1 resident, group 1's share of visit 2 in flight
+    // ---- prologue: the first two tiles are requested before the m-initialisation, which stages its summary
+    // tiles in the other half of the ring (slots 2 and 3 of the K and of the V ring: four tiles = 256 key
+    // blocks per batch), so that their latency is not paid again after it
     issue(0);
     if (nv > 1) issue(1);
+    if (!is_fa(MODE) && p.use_minit) {
+        const uint16_t* Rg = p.Krepr + ((size_t)(b * p.Hkv + hkv) * p.Tc) * D;
+        float mx = -INFINITY;
+        const int n_sum_tiles = (j_hi + BN) / BN;
+        auto stage = [&](int u) __attribute__((always_inline)) { return pp_smem + ((u & 1) + 2 + (u >> 1) * PP_STAGES) * T::BYTES; };
+        for (int t0 = 0; t0 < n_sum_tiles; t0 += 4) {
+            const int nb = min(4, n_sum_tiles - t0);
+            if (t0) __syncthreads();  // the previous batch's readers are done
+            for (int u = 0; u < nb; ++u) load_tile<D, NWV>(Rg, (t0 + u) * BN, p.Tc, stage(u), false, wave, lane);
+            wait_vm0_and_sync();
+            for (int u = 0; u < nb; ++u) {
+                qk_tile<D>(stage(u), qf, st, ql, hh);
+                mx = fmaxf(mx, tile_rowmax<true>(st, (t0 + u) * BN, j_hi_g, hh));
+            }
+        }
+        m2 = xhalf_max(mx) * p.c;
+        __syncthreads();
+    }
+    // visits 0 and 1 resident, group 1's share of visit 2 in flight
     if (grp == 1 && nv > 2) {
         issue(2);
         __builtin_amdgcn_s_waitcnt(0x0F74);
