@@ -350,22 +350,36 @@ __device__ __forceinline__ void pv_tile_pipe(const uint8_t* vt, const uint32_t* 
     __builtin_amdgcn_sched_group_barrier(0x008, DB, 0);
 }
 
-// O = O^T / l (bf16, round to nearest even), LSE = (m2 + log2 l) ln 2
+// O = O^T / l (bf16, round to nearest even), LSE = (m2 + log2 l) ln 2.
+// A lane holds, per 32-wide block of d, four runs of four consecutive elements (d = 8 q + 4 hh + 0..3) of its
+// query's row, and the lane 32 further holds the runs in between.  The two trade every second run
+// (`v_permlane32_swap`), after which each owns runs of eight: 16-byte stores, half as many store instructions
+// (the output phase of a workgroup is bound by how fast the memory pipeline takes these scattered stores).
 template <int D>
 __device__ __forceinline__ void store_output(const Params& p, const f32x16* ot, float m2, float lsum, int b, int h,
                                              int qrow, int hh) {
     const float l = xhalf_sum(lsum);
     const float inv = l > 0.f ? 1.f / l : 0.f;
+    u32x4 w[D / 32][2];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int e = 8 * u;  // first accumulator register of run 2u; run 2u + 1 starts four registers on
+            const uint32_t a0 = pack_bf16(ot[db][e] * inv, ot[db][e + 1] * inv), a1 = pack_bf16(ot[db][e + 2] * inv, ot[db][e + 3] * inv);
+            const uint32_t b0 = pack_bf16(ot[db][e + 4] * inv, ot[db][e + 5] * inv), b1 = pack_bf16(ot[db][e + 6] * inv, ot[db][e + 7] * inv);
+            // lower half lanes keep run 2u and receive the partner's run 2u (elements 16u .. 16u+7);
+            // upper half lanes receive the partner's run 2u + 1 and keep their own (elements 16u+8 .. 16u+15)
+            const auto r0 = __builtin_amdgcn_permlane32_swap(a0, b0, false, false);
+            const auto r1 = __builtin_amdgcn_permlane32_swap(a1, b1, false, false);
+            w[db][u] = u32x4{r0[0], r1[0], r0[1], r1[1]};
+        }
     if (qrow < p.N) {
         uint16_t* Og = p.O + ((size_t)(b * p.Hq + h) * p.N + qrow) * D;
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const u32x2 w = {pack_bf16(ot[db][4 * q4] * inv, ot[db][4 * q4 + 1] * inv),
-                                 pack_bf16(ot[db][4 * q4 + 2] * inv, ot[db][4 * q4 + 3] * inv)};
-                *reinterpret_cast<u32x2*>(Og + 32 * db + 8 * q4 + 4 * hh) = w;
-            }
+            for (int u = 0; u < 2; ++u) *reinterpret_cast<u32x4*>(Og + 32 * db + 16 * u + 8 * hh) = w[db][u];
         if (p.LSE && hh == 0)
             p.LSE[(size_t)(b * p.Hq + h) * p.N + qrow] = l > 0.f ? (m2 + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
     }
