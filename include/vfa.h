@@ -202,6 +202,11 @@ int vfa_fp8_pack_v(const void* V, void* Vt8, int B, int Hkv, int N, int d, float
  * scaled by 2^8 (frozen = 0) or 2^4 (frozen = 1, leaving 4 binades for scores above the frozen max;
  * beyond them exp is capped, never NaN); l sums the unrounded values; O = descale_v * (P8 V8) / l is
  * written in bf16 and LSE in fp32 as in the bf16 entry points.  Q8, K8 [B, H, N, 128] codes.
+ * With frozen = 1, a caller who quantises Q at a scale that makes descale_q * descale_k * softmax_scale *
+ * log2(e) a power of two (to 2^-18 relative) gets a faster kernel with the same result: that factor is then
+ * applied inside the matrix instruction and the frozen max enters as the accumulators' start value, so no
+ * per-score multiply or subtract is left (the performance discussion's point that a max known in advance
+ * takes vector work off the path; an online max cannot be folded this way).
  * Errors as vfa_attn_fwd; VFA_ERR_UNSUPPORTED unless d = 128, block_m = 128, block_n = 64. */
 int vfa_fp8_attn_fwd(int frozen, const void* Q8, const void* K8, const void* Vt8, void* O, float* LSE,
                      int B, int Hq, int Hkv, int N, int d, int block_m, int block_n, int causal,

@@ -1280,8 +1280,10 @@ struct Tile8 {
     __device__ static int v_off(int r, int c) { return r * 64 + ((c ^ ((r >> 2) & 3)) << 4); }
 };
 
-__device__ __forceinline__ f32x16 mfma_f8(const i32x8& a, const i32x8& b, const f32x16& c) {
-    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);  // E4M3 x E4M3, scales 2^0
+// E4M3 x E4M3; scale_a = four copies of an E8M0 exponent byte that multiplies the A operand's 32-element
+// blocks by 2^(byte - 127) inside the instruction (0x7f7f7f7f = 2^0); the B operand is not scaled
+__device__ __forceinline__ f32x16 mfma_f8(const i32x8& a, const i32x8& b, const f32x16& c, int scale_a = 0x7f7f7f7f) {
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, scale_a, 0, 0x7f7f7f7f);
 }
 
 // K tile (IS_V = false: rows of 128 bytes from a row-major [*, 128] array, rows clamped to row_limit - 1)
@@ -1320,18 +1322,19 @@ __device__ __forceinline__ i32x8 lds_frag8(const uint8_t* a0, const uint8_t* a1)
     return i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
 }
 
-// S^T tile from an E4M3 K tile: st[t][i] as in qk_tile (raw products of the codes' values)
-__device__ __forceinline__ void qk_tile8(const uint8_t* kt, const i32x8* qf, f32x16* st, int ql, int hh) {
+// S^T tile from an E4M3 K tile: st[t][i] as in qk_tile: products of the codes' values times the power of
+// two in scale_a, plus *start (a value per lane, i.e. per query, already spread over 16 registers) if given
+__device__ __forceinline__ void qk_tile8(const uint8_t* kt, const i32x8* qf, f32x16* st, int ql, int hh,
+                                         int scale_a = 0x7f7f7f7f, const f32x16* start = nullptr) {
     i32x8 f[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {  // e = 2 t + kh
         const int row = 32 * (e >> 1) + ql, c0 = 4 * (e & 1) + 2 * hh;
         f[e] = lds_frag8(kt + Tile8::k_off(row, c0), kt + Tile8::k_off(row, c0 + 1));
     }
-    st[0] = f32x16{0};
-    st[1] = f32x16{0};
 #pragma unroll
-    for (int e = 0; e < 4; ++e) st[e >> 1] = mfma_f8(f[e], qf[e & 1], st[e >> 1]);
+    for (int e = 0; e < 4; ++e)
+        st[e >> 1] = mfma_f8(f[e], qf[e & 1], (e & 1) ? st[e >> 1] : (start ? *start : f32x16{0}), scale_a);
 }
 
 __device__ __forceinline__ void pv_tile8(const uint8_t* vt, const uint32_t* pk, f32x16* ot, int lane, int hh) {
@@ -1387,6 +1390,35 @@ __device__ __forceinline__ void softmax_tile8(f32x16* st, uint32_t* pk, f32x16* 
         }
 }
 
+// The same for a frozen tile when the scores arrive as s c - m - H already (scale folded into the MFMA, the
+// rest into its accumulator start): exp, sum, convert.  Nothing per score is left of the scaling and the
+// subtraction, which the exact-max path cannot avoid because its m depends on the very tile.
+template <bool MASKED>
+__device__ __forceinline__ void softmax_tile8_folded(f32x16* st, uint32_t* pk, float& lsum, int key0, int limit, int hh) {
+    if (MASKED) {
+        const int rel = limit - key0 - 4 * hh;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) st[t][r] = (32 * t + 8 * (r >> 2) + (r & 3) <= rel) ? st[t][r] : -INFINITY;
+    }
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; r += 4) {
+            float q[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                q[e] = __builtin_amdgcn_fmed3f(__builtin_amdgcn_exp2f(st[t][r + e]), 0.f, 1.f);
+                lsum += q[e];
+            }
+            s16x2 w = {0, 0};
+            w = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(w, q[0], q[1], 0.00390625f, false);
+            w = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(w, q[2], q[3], 0.00390625f, true);
+            pk[4 * t + (r >> 2)] = __builtin_bit_cast(uint32_t, w);
+        }
+}
+
 struct Fp8Params {
     const uint8_t* Q;      // [B, Hq, N, 128] E4M3
     const uint8_t* K;      // [B, Hkv, N, 128]
@@ -1397,14 +1429,20 @@ struct Fp8Params {
     int B, Hq, Hkv, N, Tr, Tc;
     int causal, n_sink, n_local, use_minit;
     float c;          // softmax scale * descale_q * descale_k * log2(e): multiplies the raw code products
+    int scale_a;      // FOLD: that factor is a power of two and sits here as four E8M0 bytes (then c = 1)
     float descale_v;  // multiplies O
     float headroom;   // H above
 };
 
 // One workgroup = 4 waves x 32 query rows = one 128-row query block of one head; two-deep K / V^T ring
 // (32 KiB), several workgroups per CU.  MODE_FA or MODE_VFA.
-template <int MODE>
-__global__ __launch_bounds__(256, 2) void attn_fp8_kernel(const Fp8Params p) {
+// FOLD (Alg. 1 only, when the factor between code products and log2-domain scores is a power of two): the
+// K operand's block scale applies it inside every Q.K^T MFMA, and on frozen tiles the accumulators start at
+// -(m + H), so the scores come out of the matrix unit ready for exp2.
+template <int MODE, bool FOLD>
+__global__ __launch_bounds__(256, FOLD ? 3 : 2) void attn_fp8_kernel(const Fp8Params p) {
+    static_assert(!FOLD || MODE == MODE_VFA, "folding needs a max that is known before the tile");
+    const int sa = FOLD ? p.scale_a : 0x7f7f7f7f;
     constexpr int D = 128, BM = 128, DB = 4;
     __shared__ __attribute__((aligned(16))) uint8_t smem[2 * (Tile8::KBYTES + Tile8::VBYTES)];
     uint8_t* const Ks = smem;
@@ -1457,7 +1495,7 @@ __global__ __launch_bounds__(256, 2) void attn_fp8_kernel(const Fp8Params p) {
             load_tile8<false, 4>(Rg, ts * BN, p.Tc, Ks, wave, lane);
             wait_vm0_and_sync();
             f32x16 st[2];
-            qk_tile8(Ks, qf, st, ql, hh);
+            qk_tile8(Ks, qf, st, ql, hh, sa);
             mx = fmaxf(mx, tile_rowmax<true>(st, ts * BN, j_hi, hh));
         }
         m2 = xhalf_max(mx) * p.c;
@@ -1476,6 +1514,7 @@ __global__ __launch_bounds__(256, 2) void attn_fp8_kernel(const Fp8Params p) {
         load_tile8<true, 4>(Vg + (size_t)j0 * Tile8::VBYTES, 0, 0, Vs, wave, lane);
         wait_vm0_and_sync();
     }
+    f32x16 start;  // FOLD: -(m + H) of this lane's query in all 16 registers, set once the max is frozen
     // One visit; SPECIAL and MASKED are compile-time so that each of the three loops below has one softmax body.
     auto visit = [&](int k, auto special_c, auto masked_c) __attribute__((always_inline)) {
         constexpr bool SPECIAL = decltype(special_c)::value, MASKED = decltype(masked_c)::value;
@@ -1488,10 +1527,12 @@ __global__ __launch_bounds__(256, 2) void attn_fp8_kernel(const Fp8Params p) {
         f32x16 st[2];
         uint32_t pk[8];
         __builtin_amdgcn_s_setprio(1);
-        qk_tile8(Ks + buf * Tile8::KBYTES, qf, st, ql, hh);
+        if (FOLD && !SPECIAL) qk_tile8(Ks + buf * Tile8::KBYTES, qf, st, ql, hh, sa, &start);
+        else qk_tile8(Ks + buf * Tile8::KBYTES, qf, st, ql, hh, sa);
         __builtin_amdgcn_s_setprio(0);
         const bool needs_mask = (p.causal && j * BN + BN - 1 > row0) || (j + 1) * BN > N;
-        softmax_tile8<SPECIAL, MASKED>(st, pk, ot, m2, lsum, p.c, p.headroom, j * BN, needs_mask ? limit : 0x3fffffff, hh);
+        if (FOLD && !SPECIAL) softmax_tile8_folded<MASKED>(st, pk, lsum, j * BN, needs_mask ? limit : 0x3fffffff, hh);
+        else softmax_tile8<SPECIAL, MASKED>(st, pk, ot, m2, lsum, p.c, p.headroom, j * BN, needs_mask ? limit : 0x3fffffff, hh);
         __builtin_amdgcn_s_setprio(1);
         pv_tile8(Vs + buf * Tile8::VBYTES, pk, ot, lane, hh);
         __builtin_amdgcn_s_setprio(0);
@@ -1513,6 +1554,11 @@ __global__ __launch_bounds__(256, 2) void attn_fp8_kernel(const Fp8Params p) {
     }
     int k = 0;
     for (; k < n_lead; ++k) visit(k, true_type{}, true_type{});
+    if (FOLD) {
+        const float v = -(m2 + p.headroom);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) start[r] = v;
+    }
     for (; k < k_fast_end; ++k) visit(k, std::integral_constant<bool, TAIL_SPECIAL>{}, false_type{});
     for (; k < vis.total; ++k) visit(k, std::integral_constant<bool, TAIL_SPECIAL>{}, true_type{});
     // O = descale_v * 2^-8 * O^T / l (the codes of P carry 2^8); LSE = (m2 + H + log2 l) ln 2  (l sums exp2(s c - m2 - H))
@@ -1993,9 +2039,23 @@ int vfa_fp8_attn_fwd(int frozen, const void* Q8, const void* K8, const void* Vt8
     p.c = scale * descale_q * descale_k * kLog2e;
     p.descale_v = descale_v;
     p.headroom = frozen ? 4.f : 0.f;
+    // Alg. 1 with the factor between code products and log2-domain scores a power of two (the caller's choice
+    // of descale_q decides): that factor moves into the MFMA's block scale and the frozen max into its
+    // accumulator start
+    bool fold = false;
+    if (frozen) {
+        int ex = 0;
+        const float mant = frexpf(p.c, &ex);  // p.c = mant * 2^ex, mant in [0.5, 1)
+        if (fabsf(mant - 0.5f) <= 0x1p-18f && ex - 1 >= -100 && ex - 1 <= 100) {
+            fold = true;
+            p.scale_a = (127 + ex - 1) * 0x01010101;
+            p.c = 1.f;
+        }
+    }
     const dim3 grid((unsigned)(B * Hq * Tr));
-    if (frozen) attn_fp8_kernel<MODE_VFA><<<grid, 256, 0, s>>>(p);
-    else attn_fp8_kernel<MODE_FA><<<grid, 256, 0, s>>>(p);
+    if (fold) attn_fp8_kernel<MODE_VFA, true><<<grid, 256, 0, s>>>(p);
+    else if (frozen) attn_fp8_kernel<MODE_VFA, false><<<grid, 256, 0, s>>>(p);
+    else attn_fp8_kernel<MODE_FA, false><<<grid, 256, 0, s>>>(p);
     return hipGetLastError() == hipSuccess ? VFA_OK : VFA_ERR_HIP;
 }
 

@@ -32,12 +32,22 @@ def pow2_scale(x):
     return 2.0 ** math.ceil(math.log2(float(np.abs(x).max()) / 448.0))
 
 
-def quantised_problem(vfa, oracle, w, seed=wl.DEFAULT_SEED):
+def folding_scale(x, sk, d):
+    """Scale for Q that makes descale_q * descale_k * softmax_scale * log2(e) a power of two (the smallest
+    such scale that still keeps max|x| / scale <= 448): the library then moves that factor into the MFMA."""
+    rest = sk * (1.0 / math.sqrt(d)) * math.log2(math.e)
+    e = math.ceil(math.log2(float(np.abs(x).max()) / 448.0 * rest))
+    return float(np.float32(2.0 ** e / rest))
+
+
+def quantised_problem(vfa, oracle, w, seed=wl.DEFAULT_SEED, fold=False):
     import torch
     t = wl.generate(w, seed)
     Q, K, V = gpu_inputs(t)
     Qh, Kh, Vh = host_f32(t)
     sq, sk, sv = pow2_scale(Qh), pow2_scale(Kh), pow2_scale(Vh)
+    if fold:
+        sq = folding_scale(Qh, sk, w.d)
     Q8, K8 = vfa.fp8_quantize(Q, 1 / sq), vfa.fp8_quantize(K, 1 / sk)
     Vt8 = vfa.fp8_pack_v(V, 1 / sv)
     torch.cuda.synchronize()
@@ -97,6 +107,38 @@ def test_fp8_attention_matches_oracle_on_dequantised_operands(vfa, oracle, name,
         gap = (Me - ref["m_final"])[~np.isnan(Me)]
         print(name, "true max above frozen max (nats): max %.2f (headroom 2.77)" % gap.max(), flush=True)
         assert gap.max() < 2.77
+
+
+@pytest.mark.parametrize("name,w", SHAPES, ids=[s[0] for s in SHAPES])
+def test_fp8_folded_scale_matches_oracle(vfa, oracle, name, w):
+    """Alg. 1 with Q quantised so that the factor between code products and log2-domain scores is a power of
+    two: the library then applies it inside the MFMA and starts the accumulators of frozen tiles at -(m + H).
+    Same bars as the unfolded path, against the oracle on these (differently scaled) dequantised operands; and
+    the two paths must agree with each other on the SAME operands when the fold is defeated by one ulp."""
+    import torch
+    pr = quantised_problem(vfa, oracle, w, fold=True)
+    assert np.array_equal(pr["Q8"].cpu().numpy(), pr["cq"])
+    blocks = wl.all_blocks(w)
+    Oe, Le, Me = oracle.exact(pr["Qd"], pr["Kd"], pr["Vd"], w.block_m, w.causal, blocks)
+    vmax = float(np.abs(pr["Vd"]).max())
+    kw = dict(descale_k=pr["sk"], descale_v=pr["sv"], block_m=w.block_m, block_n=w.block_n, causal=w.causal,
+              frozen=True, n_sink=w.n_sink, n_local=w.n_local)
+    O, L = vfa.fp8_attn_fwd(pr["Q8"], pr["K8"], pr["Vt8"], descale_q=pr["sq"], **kw)
+    torch.cuda.synchronize()
+    got_O, got_L = gather_blocks(O, blocks, w.block_m, w.N), gather_blocks(L, blocks, w.block_m, w.N)
+    valid = ~np.isnan(Le)
+    assert not np.isnan(got_O[valid]).any()
+    err = np.abs(got_O[valid] - Oe[valid])
+    lerr = np.abs(got_L[valid] - Le[valid]).max()
+    print(name, "folded max_abs %.4f mean_abs %.5f lse %.2e (bound %.3f)" % (err.max(), err.mean(), lerr, vmax / 16), flush=True)
+    assert err.max() <= vmax / 16 * 1.05 + 2e-2 and err.mean() <= vmax / 16 / 8 and lerr <= LSE_ABS
+    # descale_q off by 2^-12: no power of two any more, so the ordinary path runs, on scores 2^-12 (relative) apart
+    O2, L2 = vfa.fp8_attn_fwd(pr["Q8"], pr["K8"], pr["Vt8"], descale_q=pr["sq"] * (1 + 2.0 ** -12), **kw)
+    torch.cuda.synchronize()
+    dO = (O.float() - O2.float()).abs().max().item()
+    dL = (L - L2).abs().max().item()
+    print(name, "folded vs unfolded: max |dO| %.4f max |dLSE| %.2e" % (dO, dL), flush=True)
+    assert dO <= vmax / 16 + 2e-2 and dL <= 2e-2
 
 
 def test_fp8_frozen_max_far_too_low_is_capped_not_nan(vfa, oracle):
