@@ -143,14 +143,20 @@ def test_vsa_mask_bit_exact_and_output(vfa, oracle, name, w, thr):
     assert sparsity > 0.02
 
 
-def test_vsa_huge_threshold_equals_vfa_bitwise(vfa):
+def test_vsa_huge_threshold_equals_vfa(vfa):
+    """With a threshold nothing reaches Alg. 2 is Alg. 1.  The two kernels add a tile's row sum into l in a
+    different order (Alg. 2 commits each tile's sum as one number once the block's decision is known), so
+    the results agree to fp32 rounding of l, not bit for bit: one bf16 ulp in O, 1e-5 in LSE."""
     import torch
     w = W(B=1, Hq=2, Hkv=1, N=1024)
     Q, K, V = gpu_inputs(wl.generate(w))
     O1, L1 = vfa.vfa_attn_fwd(Q, K, V)
     O2, L2, M = vfa.vsa_attn_fwd(Q, K, V, skip_threshold_nats=1e4)
     torch.cuda.synchronize()
-    assert torch.equal(O1, O2) and torch.equal(L1, L2)
+    o1, o2 = O1.float(), O2.float()
+    assert ((o1 - o2).abs() <= 2.0 ** -7 * torch.maximum(o1.abs(), o2.abs()) + 1e-30).all()  # <= 1 ulp of bf16
+    assert (o1 != o2).float().mean().item() < 0.02
+    assert (L1 - L2).abs().max().item() <= 1e-5
     assert int((M == 1).sum()) == 0
 
 
