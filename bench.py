@@ -26,7 +26,7 @@ from paper_2604_12798_amd import workloads as wl  # noqa: E402
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
 # measured HBM bytes of one VFA attention launch: (FETCH_SIZE KiB * 1.954 + WRITE_SIZE KiB * 1.0) * 1024
-TRAFFIC_BYTES = {"cfg3": int((4.504e5 * 1.954 + 2.663e5) * 1024)}
+TRAFFIC_BYTES = {"cfg3": int((4.492e5 * 1.954 + 2.662e5) * 1024)}
 METRIC = "attn fwd TFLOP/s + % MFMA bf16 peak, VFA/VSA vs online-softmax baseline"
 
 
