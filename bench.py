@@ -181,6 +181,10 @@ def main():
         ms_lz = time_region(run_fa_lazy, args.steps, args.warmup)   # second baseline: conditional rescale, tau = 8
         out["baseline_fa_lazy_rescale"] = {"ms_per_step": ms_lz, "tflops": dense / ms_lz / 1e9, "rescale_tau": 8.0,
                                            "speedup_vfa_vs_this": ms_lz / ms_vfa}
+        # the same with every second exponential computed in software (the other half of that related work's recipe)
+        ms_se = time_region(lambda: vfa.fa_lazy_rescale_softexp_fwd(Q, K, V, rescale_tau=8.0, **kw), args.steps, args.warmup)
+        out["baseline_fa_lazy_rescale_softexp"] = {"ms_per_step": ms_se, "tflops": dense / ms_se / 1e9, "rescale_tau": 8.0,
+                                                   "software_exp2_share": 0.5, "speedup_vfa_vs_this": ms_se / ms_vfa}
     if "vsa" in only:
         ms_vsa = time_region(run_vsa, args.steps, args.warmup)
         torch.cuda.synchronize()

@@ -80,6 +80,15 @@ int fa_lazy_rescale_fwd(const void* Q, const void* K, const void* V, void* O, fl
                         int Hq, int Hkv, int N, int d, int block_m, int block_n, int causal,
                         float softmax_scale, float rescale_tau, void* stream);
 
+/* The second baseline with the other half of the same related work's recipe (FlashAttention-4, software
+ * exponential): as fa_lazy_rescale_fwd, and every second exponential of a tile is computed without the
+ * transcendental unit (range reduction, a cubic for 2^fraction on [0, 1) with relative error <= 2.1e-4,
+ * the integer part added into the exponent field).  The result is the same attention to that error, far
+ * below the bf16 rounding of P.  Same arguments, layouts and errors as fa_lazy_rescale_fwd. */
+int fa_lazy_rescale_softexp_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
+                                int Hq, int Hkv, int N, int d, int block_m, int block_n, int causal,
+                                float softmax_scale, float rescale_tau, void* stream);
+
 /* VFA forward (Alg. 1).  For each query block: the running max starts at
  * m_init = max_j scale * Q_i . Krepr_j over the visible key blocks (use_minit = 1: the summaries
  * are computed into `workspace` first; use_minit = 2: `workspace` already holds them, e.g. from

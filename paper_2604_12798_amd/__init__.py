@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libvfa.so")
 _lib = None
 
 EXPORTS = ("vfa_workspace_bytes", "vfa_kblock_summary", "vfa_kblock_summary_mode", "fa_baseline_fwd",
-           "fa_lazy_rescale_fwd", "vfa_attn_fwd", "vsa_attn_fwd", "vfa_variant_fwd", "vfa_kblock_summary_append",
+           "fa_lazy_rescale_fwd", "fa_lazy_rescale_softexp_fwd", "vfa_attn_fwd", "vsa_attn_fwd", "vfa_variant_fwd", "vfa_kblock_summary_append",
            "vfa_decode_workspace_bytes", "vfa_decode_fwd", "vfa_kblock_summary_append_varlen", "vfa_decode_varlen_fwd", "vfa_fp8_quantize", "vfa_fp8_v_bytes", "vfa_fp8_pack_v",
            "vfa_fp8_attn_fwd", "vfa_strerror")
 
@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.fa_baseline_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, f, vp]
         L.fa_lazy_rescale_fwd.restype = i
         L.fa_lazy_rescale_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, f, f, vp]
+        L.fa_lazy_rescale_softexp_fwd.restype = i
+        L.fa_lazy_rescale_softexp_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, f, f, vp]
         L.vfa_attn_fwd.restype = i
         L.vfa_attn_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, i, i, f, vp, sz, vp]
         L.vsa_attn_fwd.restype = i
@@ -147,6 +149,18 @@ def fa_lazy_rescale_fwd(Q, K, V, *, block_m=128, block_n=64, causal=True, softma
                                    int(bool(causal)), float(softmax_scale), float(rescale_tau), _stream(stream))
     if rc != 0:
         raise VfaError(rc, "fa_lazy_rescale_fwd")
+    return O, L
+
+
+def fa_lazy_rescale_softexp_fwd(Q, K, V, *, block_m=128, block_n=64, causal=True, softmax_scale=0.0, rescale_tau=8.0,
+                                out=None, lse=None, want_lse=True, stream=None):
+    B, Hq, Hkv, N, d = _check_qkv(Q, K, V)
+    O, L = _outputs(Q, out, lse, want_lse)
+    rc = lib().fa_lazy_rescale_softexp_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(L), B, Hq, Hkv, N, d, block_m,
+                                           block_n, int(bool(causal)), float(softmax_scale), float(rescale_tau),
+                                           _stream(stream))
+    if rc != 0:
+        raise VfaError(rc, "fa_lazy_rescale_softexp_fwd")
     return O, L
 
 

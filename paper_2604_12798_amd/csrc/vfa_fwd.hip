@@ -34,9 +34,16 @@ constexpr int BN = 64;  // keys per tile (= block_n)
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-enum Mode { MODE_FA = 0, MODE_VFA = 1, MODE_VSA = 2, MODE_FA_LAZY = 3 };
+enum Mode { MODE_FA = 0, MODE_VFA = 1, MODE_VSA = 2, MODE_FA_LAZY = 3, MODE_FA_SOFTEXP = 4 };
 // the two online-softmax baselines: ascending order, row max on every tile, no summaries
-constexpr bool is_fa(int mode) { return mode == MODE_FA || mode == MODE_FA_LAZY; }
+constexpr bool is_fa(int mode) { return mode == MODE_FA || mode == MODE_FA_LAZY || mode == MODE_FA_SOFTEXP; }
+constexpr bool is_lazy(int mode) { return mode == MODE_FA_LAZY || mode == MODE_FA_SOFTEXP; }
+// MODE_FA_SOFTEXP: every SOFTEXP_EVERY-th exponential of a tile is computed with ordinary vector instructions
+#ifndef VFA_SOFTEXP_EVERY
+#define VFA_SOFTEXP_EVERY 2
+#endif
+constexpr int SOFTEXP_EVERY = VFA_SOFTEXP_EVERY;
+constexpr int softexp_every(int mode) { return mode == MODE_FA_SOFTEXP ? SOFTEXP_EVERY : 0; }
 
 struct Params {
     const uint16_t* Q;
@@ -203,6 +210,18 @@ __device__ __forceinline__ float tile_rowmax(const f32x16* st, int key0, int lim
     return mx;
 }
 
+// 2^x without the transcendental unit (related work: FlashAttention-4's software exponential): split x into
+// integer and fraction, a cubic for 2^fraction on [0, 1) (p(0) = 1 exactly, relative error <= 2.1e-4, far below
+// the bf16 rounding of P), and the integer added into the exponent field.  x <= about 2^7; -inf gives 2^-126.
+__device__ __forceinline__ float exp2_soft(float x) {
+    const float xc = fmaxf(x, -126.f);
+    const float n = __builtin_floorf(xc);
+    const float f = xc - n;  // in [0, 1]; exactly 1 only for a tiny negative xc, where q(1) 2^-1 is still right
+                             // (the fraction instruction would return 1 there too, but then n must not be derived from it)
+    const float q = __builtin_fmaf(__builtin_fmaf(__builtin_fmaf(0.07764090f, f, 0.22760449f), f, 0.69466668f), f, 1.0f);
+    return __uint_as_float(__float_as_uint(q) + ((uint32_t)(int)n << 23));
+}
+
 // Softmax step of one tile for this lane's query: st (raw scores) -> pk (exp, bf16 pairs),
 // lsum += row sum.  SPECIAL: exact online-softmax update of m2 with rescale of lsum and ot;
 // otherwise m2 is frozen: no row max, no rescale (Alg. 1 / Table 1).
@@ -212,7 +231,8 @@ __device__ __forceinline__ float tile_rowmax(const f32x16* st, int key0, int lim
 // more than tau2; otherwise it keeps the old max and its scale factor is exactly 1, and when that
 // holds for every row of the wave the whole rescale (lsum and the 16 * DB accumulator registers) is
 // branched over.  exp(S - m) may then reach 2^tau2, which bf16 / fp32 hold without trouble.
-template <bool SPECIAL, bool MASKED, int DB, bool RESCALE = true, bool LAZY = false>
+// SOFT_EVERY > 0: of every SOFT_EVERY consecutive exponentials one is computed by exp2_soft.
+template <bool SPECIAL, bool MASKED, int DB, bool RESCALE = true, bool LAZY = false, int SOFT_EVERY = 0>
 __device__ __forceinline__ void softmax_tile(f32x16* st, uint32_t* pk, f32x16* ot, float& m2, float& lsum, float c,
                                              int key0, int limit, int hh, float tau2 = 0.f) {
     if (MASKED) {
@@ -244,8 +264,9 @@ __device__ __forceinline__ void softmax_tile(f32x16* st, uint32_t* pk, f32x16* o
     for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int r = 0; r < 16; r += 2) {
-            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[t][r], c, -msub));
-            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[t][r + 1], c, -msub));
+            const float x0 = __builtin_fmaf(st[t][r], c, -msub), x1 = __builtin_fmaf(st[t][r + 1], c, -msub);
+            const float p0 = (SOFT_EVERY > 0 && (16 * t + r) % SOFT_EVERY == 0) ? exp2_soft(x0) : __builtin_amdgcn_exp2f(x0);
+            const float p1 = (SOFT_EVERY > 0 && (16 * t + r + 1) % SOFT_EVERY == 0) ? exp2_soft(x1) : __builtin_amdgcn_exp2f(x1);
             lsum += p0;
             lsum += p1;
             pk[8 * t + (r >> 1)] = pack_bf16(p0, p1);
@@ -533,9 +554,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const Params p) {
             if (special) {
                 // (VSA takes the conditional-rescale form too; its tau2 is negative unless the variant asks for it,
                 // and then only the branch over an all-ones rescale is left of it)
-                constexpr bool LAZY = MODE == MODE_FA_LAZY || MODE == MODE_VSA;
-                if (masked) softmax_tile<true, true, DB, true, LAZY>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh, p.tau2);
-                else softmax_tile<true, false, DB, true, LAZY>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh, p.tau2);
+                constexpr bool LAZY = is_lazy(MODE) || MODE == MODE_VSA;
+                constexpr int SE = softexp_every(MODE);
+                if (masked) softmax_tile<true, true, DB, true, LAZY, SE>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh, p.tau2);
+                else softmax_tile<true, false, DB, true, LAZY, SE>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh, p.tau2);
             } else {
                 if (masked) softmax_tile<false, true, DB>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh);
                 else softmax_tile<false, false, DB>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh);
@@ -841,11 +863,11 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
         pv_pending = keep;
         if (keep) {
             if (FAST)
-                softmax_tile<SPECIAL, false, DB, !FIRST, MODE == MODE_FA_LAZY>(st, pk, ot, m2, lsum, p.c, j * BN, limit, hh,
-                                                                               p.tau2);
+                softmax_tile<SPECIAL, false, DB, !FIRST, is_lazy(MODE), softexp_every(MODE)>(st, pk, ot, m2, lsum, p.c, j * BN,
+                                                                                             limit, hh, p.tau2);
             else
-                softmax_tile<SPECIAL, true, DB, !FIRST, MODE == MODE_FA_LAZY>(st, pk, ot, m2, lsum, p.c, j * BN,
-                                                                              tile_masked(j) ? limit : 0x3fffffff, hh, p.tau2);
+                softmax_tile<SPECIAL, true, DB, !FIRST, is_lazy(MODE), softexp_every(MODE)>(
+                    st, pk, ot, m2, lsum, p.c, j * BN, tile_masked(j) ? limit : 0x3fffffff, hh, p.tau2);
             ld_v(fa, Vs + (k & 3) * T::BYTES, 0);  // first fragments of the coming P.V, in flight over the barrier
         }
         if (is_fa(MODE)) __builtin_amdgcn_s_setprio(0);
@@ -1882,7 +1904,7 @@ int vfa_vsa_common(int mode, const void* Q, const void* K, const void* V, void* 
     return mode == MODE_VSA ? launch_fwd<MODE_VSA>(p, d, block_m, s) : launch_fwd<MODE_VFA>(p, d, block_m, s);
 }
 
-int fa_common(bool lazy, const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv,
+int fa_common(int mode, const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv,
               int N, int d, int block_m, int block_n, int causal, float softmax_scale, float tau, void* stream) {
     int rc = check_common(Q, K, V, O, LSE, B, Hq, Hkv, N, d, block_m, block_n);
     if (rc != VFA_OK) return rc;
@@ -1896,8 +1918,9 @@ int fa_common(bool lazy, const void* Q, const void* K, const void* V, void* O, f
     const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)d);
     p.c = scale * kLog2e;
     p.tau2 = tau;  // tau is already a count of factors of two: tau * ln 2 nats = tau in the log2 domain
-    return lazy ? launch_fwd<MODE_FA_LAZY>(p, d, block_m, (hipStream_t)stream)
-                : launch_fwd<MODE_FA>(p, d, block_m, (hipStream_t)stream);
+    if (mode == MODE_FA_SOFTEXP) return launch_fwd<MODE_FA_SOFTEXP>(p, d, block_m, (hipStream_t)stream);
+    if (mode == MODE_FA_LAZY) return launch_fwd<MODE_FA_LAZY>(p, d, block_m, (hipStream_t)stream);
+    return launch_fwd<MODE_FA>(p, d, block_m, (hipStream_t)stream);
 }
 
 int decode_common(const void* Q, const void* K, const void* V, const void* Krepr, void* O, float* LSE, int B, int Hq,
@@ -1931,15 +1954,23 @@ int vfa_kblock_summary_mode(const void* K, void* Krepr, int B, int Hkv, int N, i
 
 int fa_baseline_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int N,
                     int d, int block_m, int block_n, int causal, float softmax_scale, void* stream) {
-    return fa_common(false, Q, K, V, O, LSE, B, Hq, Hkv, N, d, block_m, block_n, causal, softmax_scale, 0.f, stream);
+    return fa_common(MODE_FA, Q, K, V, O, LSE, B, Hq, Hkv, N, d, block_m, block_n, causal, softmax_scale, 0.f, stream);
 }
 
 int fa_lazy_rescale_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv,
                         int N, int d, int block_m, int block_n, int causal, float softmax_scale, float rescale_tau,
                         void* stream) {
     if (!(rescale_tau >= 0.f && isfinite(rescale_tau))) return VFA_ERR_INVALID_ARG;
-    return fa_common(true, Q, K, V, O, LSE, B, Hq, Hkv, N, d, block_m, block_n, causal, softmax_scale, rescale_tau,
+    return fa_common(MODE_FA_LAZY, Q, K, V, O, LSE, B, Hq, Hkv, N, d, block_m, block_n, causal, softmax_scale, rescale_tau,
                      stream);
+}
+
+int fa_lazy_rescale_softexp_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv,
+                                int N, int d, int block_m, int block_n, int causal, float softmax_scale,
+                                float rescale_tau, void* stream) {
+    if (!(rescale_tau >= 0.f && isfinite(rescale_tau))) return VFA_ERR_INVALID_ARG;
+    return fa_common(MODE_FA_SOFTEXP, Q, K, V, O, LSE, B, Hq, Hkv, N, d, block_m, block_n, causal, softmax_scale,
+                     rescale_tau, stream);
 }
 
 int vfa_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int N,

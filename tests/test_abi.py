@@ -58,6 +58,12 @@ def test_bad_arguments_are_rejected_before_launch(pkg):
     assert lz(p, p, p, p, none, *ok_shape, 0.0, float("inf"), none) == -1
     assert lz(none, p, p, p, none, *ok_shape, 0.0, 8.0, none) == -1
     assert lz(p, p, p, p, none, 0, 4, 2, 256, 128, 128, 64, 1, 0.0, 8.0, none) == 0
+    se = lambda *a: L.fa_lazy_rescale_softexp_fwd(*a)
+    assert se(p, p, p, p, none, *ok_shape, 0.0, -1.0, none) == -1
+    assert se(p, p, p, p, none, *ok_shape, 0.0, float("nan"), none) == -1
+    assert se(none, p, p, p, none, *ok_shape, 0.0, 8.0, none) == -1
+    assert se(p, p, p, p, none, 1, 4, 2, 256, 96, 128, 64, 1, 0.0, 8.0, none) == -2
+    assert se(p, p, p, p, none, 0, 4, 2, 256, 128, 128, 64, 1, 0.0, 8.0, none) == 0
     vf = lambda *a: L.vfa_attn_fwd(*a)
     base = (p, p, p, p, none, *ok_shape)
     assert vf(*base, 1, 1, 1, 0.0, none, 0, none) == -1                           # workspace missing

@@ -35,6 +35,9 @@ def test_full_size_sampled_blocks(oracle, name, n_random):
     O, L = vfa.fa_lazy_rescale_fwd(Q, K, V, rescale_tau=8.0, **kw)
     torch.cuda.synchronize()
     print(name, "fa_lazy", check_o_lse(O, L, Oe, Le, blocks, w.block_m, w.N, "fa_lazy_rescale_fwd vs exact"), flush=True)
+    O, L = vfa.fa_lazy_rescale_softexp_fwd(Q, K, V, rescale_tau=8.0, **kw)
+    torch.cuda.synchronize()
+    print(name, "fa_softexp", check_o_lse(O, L, Oe, Le, blocks, w.block_m, w.N, "fa_lazy_rescale_softexp_fwd vs exact"), flush=True)
     del O, L
     krepr = oracle.sabsmax(Kh, w.block_n)
     ref = oracle.blocks(Qh, Kh, Vh, w.block_m, w.block_n, w.causal, blocks, n_sink=w.n_sink, n_local=w.n_local, krepr=krepr)

@@ -61,6 +61,9 @@ def _run_all(vfa, w, t, blocks, oracle, use_minit=True):
         O, L = vfa.fa_lazy_rescale_fwd(Q, K, V, rescale_tau=tau, **kw)
         torch.cuda.synchronize()
         res["fa_lazy%g" % tau] = check_o_lse(O, L, Oe, Le, blocks, w.block_m, w.N, "fa_lazy_rescale_fwd vs exact")
+    O, L = vfa.fa_lazy_rescale_softexp_fwd(Q, K, V, rescale_tau=8.0, **kw)   # half of the exponentials in software
+    torch.cuda.synchronize()
+    res["fa_softexp"] = check_o_lse(O, L, Oe, Le, blocks, w.block_m, w.N, "fa_lazy_rescale_softexp_fwd vs exact")
     O, L = vfa.vfa_attn_fwd(Q, K, V, n_sink=w.n_sink, n_local=w.n_local, use_minit=use_minit, **kw)
     torch.cuda.synchronize()
     ref = oracle.blocks(Qh, Kh, Vh, w.block_m, w.block_n, w.causal, blocks, n_sink=w.n_sink, n_local=w.n_local,
