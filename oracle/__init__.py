@@ -107,9 +107,11 @@ def visit_list(N, block_m, block_n, causal, i, n_sink, n_local, reorder=True):
 
 def blocks(Q, K, V, block_m, block_n, causal, blocks, *, n_sink=1, n_local=1, use_minit=True,
            reorder=True, freeze=True, vsa=False, skip_threshold_nats=None, scale=None,
-           krepr=None, m_override=None, want_traj=False):
+           krepr=None, qrepr=None, m_override=None, want_traj=False):
     """Alg. 1 (default), Alg. 2 (vsa=True) or online softmax on every block
     (use_minit=False, reorder=False, freeze=False) for the listed query blocks.
+    qrepr [B,Hq,Tr,d] (e.g. sabsmax(Q, block_m, mode)) switches the m-initialisation to the block-wise
+    score of the ablation study: one summary vector per query block, one seed for all its rows.
     Returns a dict: O, LSE, m_init, m_final, mask, margin, counters[, traj]."""
     Q, K, V = _f32(Q), _f32(K), _f32(V)
     B, Hq, Hkv, N, d = _dims(Q, K)
@@ -121,6 +123,9 @@ def blocks(Q, K, V, block_m, block_n, causal, blocks, *, n_sink=1, n_local=1, us
         krepr = sabsmax(K, block_n)
     if krepr is not None:
         krepr = np.ascontiguousarray(krepr, dtype=np.float64)
+    if qrepr is not None:
+        qrepr = np.ascontiguousarray(qrepr, dtype=np.float64)
+        assert qrepr.shape == (B, Hq, -(-N // block_m), d)
     if m_override is not None:
         m_override = np.ascontiguousarray(m_override, dtype=np.float64)
         assert m_override.shape == (n, block_m)
@@ -132,10 +137,10 @@ def blocks(Q, K, V, block_m, block_n, causal, blocks, *, n_sink=1, n_local=1, us
     mask = np.zeros((n, Tc), dtype=np.uint8); margin = np.empty((n, Tc))
     cnt = np.zeros((n, 4), dtype=np.int64)
     traj = np.full((n, Tc, block_m, 2), np.nan) if want_traj else None
-    rc = _load().oracle_blocks(
+    rc = _load().oracle_blocks_qrepr(
         _p(Q, ctypes.c_float), _p(K, ctypes.c_float), _p(V, ctypes.c_float), B, Hq, Hkv, N, d,
         block_m, block_n, int(causal), ctypes.c_double(scale), _p(krepr, ctypes.c_double),
-        n_sink, n_local, int(use_minit), int(reorder), int(freeze), int(vsa), ctypes.c_double(ln_lambda),
+        _p(qrepr, ctypes.c_double), n_sink, n_local, int(use_minit), int(reorder), int(freeze), int(vsa), ctypes.c_double(ln_lambda),
         n, _p(blk, ctypes.c_int), _p(m_override, ctypes.c_double), _p(O, ctypes.c_double), _p(L, ctypes.c_double),
         _p(mi, ctypes.c_double), _p(mf, ctypes.c_double), _p(mask, ctypes.c_uint8), _p(margin, ctypes.c_double),
         _p(cnt, ctypes.c_int64), _p(traj, ctypes.c_double))

@@ -236,6 +236,8 @@ typedef struct {
     double ln_lambda;
     double lazy_tau; /* < 0: off; else keep the old max while it grows by at most lazy_tau * ln 2 */
     int rowskip;     /* with vsa: rows that fail the threshold test drop out of a kept tile */
+    const double *qrepr; /* NULL, or [B,Hq,Tr,d]: one summary vector per query block replaces the rows of
+                          * Q_i in the approximate score (ablation "block-wise approximation on Q") */
 } opts_t;
 
 static void one_block(const prob_t *p, const opts_t *o, const double *krepr, int b, int h, int i,
@@ -256,15 +258,19 @@ static void one_block(const prob_t *p, const opts_t *o, const double *krepr, int
     double *mt = (double *)malloc((size_t)Br * sizeof(double));
     int *vj = (int *)malloc((size_t)Tc * sizeof(int)), *vs = (int *)malloc((size_t)Tc * sizeof(int));
 
-    /* m-initialisation (Alg. 1: score_approx = Q_i k_repr_j^T, elementwise max over j) */
+    /* m-initialisation (Alg. 1: score_approx = Q_i k_repr_j^T, elementwise max over j).  In the
+     * block-wise ablation the score is q_repr_i k_repr_j^T, one scalar per key block, and every
+     * row of the query block starts from the same maximum. */
     for (int rr = 0; rr < nr; ++rr) {
         double mi = -INFINITY;
         if (o->use_minit) {
             const float *q = q_row(p, b, h, r0 + rr);
+            const double *qr = o->qrepr
+                ? o->qrepr + (((size_t)b * p->Hq + h) * ceil_div(N, Br) + i) * d : NULL;
             for (int j = 0; j <= j_hi; ++j) {
                 const double *kr = krepr + (((size_t)b * p->Hkv + hkv) * Tc + j) * d;
                 double a = 0.0;
-                for (int t = 0; t < d; ++t) a += (double)q[t] * kr[t];
+                for (int t = 0; t < d; ++t) a += (qr ? qr[t] : (double)q[t]) * kr[t];
                 mi = fmax(mi, p->scale * a);
             }
         }
@@ -393,16 +399,42 @@ static void one_block(const prob_t *p, const opts_t *o, const double *krepr, int
  *   counters    [nblk, 4] int64: tiles visited, rowmax executions, rescale executions, skipped
  *   traj        NULL or [nblk, Tc, block_m, 2]: (m, l) after the k-th visited block
  * FA is (use_minit=0, reorder=0, freeze=0, vsa=0).                       */
+int oracle_blocks_qrepr(const float *Q, const float *K, const float *V, int B, int Hq, int Hkv, int N,
+                        int d, int block_m, int block_n, int causal, double scale, const double *krepr,
+                        const double *qrepr, int n_sink, int n_local, int use_minit, int reorder,
+                        int freeze, int vsa, double ln_lambda, int nblk, const int *blocks,
+                        const double *m_override, double *O, double *LSE, double *m_init_out,
+                        double *m_final_out, uint8_t *mask_out, double *margin_out,
+                        int64_t *counters, double *traj);
+
 int oracle_blocks(const float *Q, const float *K, const float *V, int B, int Hq, int Hkv, int N,
                   int d, int block_m, int block_n, int causal, double scale, const double *krepr,
                   int n_sink, int n_local, int use_minit, int reorder, int freeze, int vsa,
                   double ln_lambda, int nblk, const int *blocks, const double *m_override,
                   double *O, double *LSE, double *m_init_out, double *m_final_out,
                   uint8_t *mask_out, double *margin_out, int64_t *counters, double *traj) {
+    return oracle_blocks_qrepr(Q, K, V, B, Hq, Hkv, N, d, block_m, block_n, causal, scale, krepr, NULL,
+                               n_sink, n_local, use_minit, reorder, freeze, vsa, ln_lambda, nblk,
+                               blocks, m_override, O, LSE, m_init_out, m_final_out, mask_out,
+                               margin_out, counters, traj);
+}
+
+/* oracle_blocks with the left operand of the approximate score ablated (Experiments, "Replacing
+ * row-wise approximation with block-wise approximation on Q"): qrepr [B,Hq,ceil(N/block_m),d] holds
+ * one summary of each query block (oracle_sabsmax applied to Q with block_m gives the three
+ * summaries the ablation table lists); the score q_repr_i . k_repr_j is broadcast to all rows of
+ * block i.  qrepr = NULL is the row-wise method. */
+int oracle_blocks_qrepr(const float *Q, const float *K, const float *V, int B, int Hq, int Hkv, int N,
+                        int d, int block_m, int block_n, int causal, double scale, const double *krepr,
+                        const double *qrepr, int n_sink, int n_local, int use_minit, int reorder,
+                        int freeze, int vsa, double ln_lambda, int nblk, const int *blocks,
+                        const double *m_override, double *O, double *LSE, double *m_init_out,
+                        double *m_final_out, uint8_t *mask_out, double *margin_out,
+                        int64_t *counters, double *traj) {
     if (Hq % Hkv != 0 || block_m <= 0 || block_n <= 0) return -1;
     if (use_minit && !krepr && !m_override) return -1;
     prob_t p = {Q, K, V, B, Hq, Hkv, N, d, block_m, block_n, causal, scale};
-    opts_t o = {n_sink, n_local, use_minit, reorder, freeze, vsa, ln_lambda, -1.0, 0};
+    opts_t o = {n_sink, n_local, use_minit, reorder, freeze, vsa, ln_lambda, -1.0, 0, qrepr};
     const int Tc = ceil_div(N, block_n);
 #pragma omp parallel for schedule(dynamic, 1)
     for (int n = 0; n < nblk; ++n) {

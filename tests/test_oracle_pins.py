@@ -169,6 +169,71 @@ def test_m_init_is_max_of_q_dot_summaries(oracle):
             assert np.abs(out["m_init"][n] - approx.max(1)).max() < 1e-13
 
 
+# ------------------------------------------------------------------ block-wise q_repr ablation
+def test_blockwise_q_repr_hand_worked(oracle):
+    """One query block [[1,-2],[-3,1]], one key block holding [2,1] twice, scale 1 (values worked by hand):
+    absmax(Q) = [3,2], sabsmax(Q) = [-3,-2], mean(Q) = [-1,-0.5]; k_repr = [2,1];
+    seeds 8, -8, -2.5 for both rows, where the row-wise method gives 0 and -5."""
+    Q = np.array([[1, -2], [-3, 1]], np.float32).reshape(1, 1, 2, 2)
+    K = np.array([[2, 1], [2, 1]], np.float32).reshape(1, 1, 2, 2)   # the key twice, as one block
+    V = np.array([[1, 0], [0, 1]], np.float32).reshape(1, 1, 2, 2)
+    blocks = np.array([(0, 0, 0)], np.int32)
+    kw = dict(n_sink=0, n_local=0, scale=1.0)
+    assert np.array_equal(oracle.blocks(Q, K, V, 2, 2, False, blocks, **kw)["m_init"][0], [0.0, -5.0])
+    for mode, seed in ((3, 8.0), (0, -8.0), (2, -2.5)):
+        qr = oracle.sabsmax(Q, 2, mode)
+        out = oracle.blocks(Q, K, V, 2, 2, False, blocks, qrepr=qr, **kw)
+        assert np.array_equal(out["m_init"][0], [seed, seed]), (mode, out["m_init"])
+        # both keys equal: O is the mean of V's rows whatever the seed, LSE = s + ln 2
+        assert np.abs(out["O"][0] - 0.5).max() < 1e-15
+        assert np.abs(out["LSE"][0] - (np.array([0.0, -5.0]) + math.log(2))).max() < 1e-14
+
+
+def test_blockwise_q_repr_reduces_to_rowwise_for_constant_blocks(oracle):
+    """If all rows of a query block are the same vector, its signed-absmax and its mean are that vector,
+    so the block-wise seed equals the row-wise one; the unsigned summary agrees where Q >= 0."""
+    B, Hq, Hkv, N, d, bm, bn = 1, 2, 1, 64, 6, 16, 8
+    rows = rnd(70, B, Hq, N // bm, 1, d)
+    Q = np.broadcast_to(rows, (B, Hq, N // bm, bm, d)).reshape(B, Hq, N, d).copy()
+    K, V = rnd(71, B, Hkv, N, d), rnd(72, B, Hkv, N, d)
+    blocks = np.array([(0, h, i) for h in range(Hq) for i in range(N // bm)], np.int32)
+    for causal in (False, True):
+        row = oracle.blocks(Q, K, V, bm, bn, causal, blocks)
+        for mode in (0, 2):
+            blk = oracle.blocks(Q, K, V, bm, bn, causal, blocks, qrepr=oracle.sabsmax(Q, bm, mode))
+            assert np.abs(blk["m_init"] - row["m_init"]).max() < 1e-13
+            assert np.abs(blk["O"] - row["O"]).max() < 1e-13
+        Qp = np.abs(Q)
+        rowp = oracle.blocks(Qp, K, V, bm, bn, causal, blocks)
+        blkp = oracle.blocks(Qp, K, V, bm, bn, causal, blocks, qrepr=oracle.sabsmax(Qp, bm, 3))
+        assert np.abs(blkp["m_init"] - rowp["m_init"]).max() < 1e-13
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_blockwise_q_repr_seed_is_broadcast_and_result_stays_exact(oracle, causal):
+    """The seed is one scalar per (query block, visible key blocks): recomputed here from library
+    reductions over the block; rows of a block share it; a ragged last block summarises its valid
+    rows only; and the attention output is still the exact one (the seed cancels in O / l)."""
+    B, Hq, Hkv, N, d, bm, bn = 1, 4, 2, 90, 8, 16, 8
+    Q, K, V = rnd(73, B, Hq, N, d), rnd(74, B, Hkv, N, d), rnd(75, B, Hkv, N, d)
+    Tr = -(-N // bm)
+    blocks = np.array([(0, h, i) for h in range(Hq) for i in range(Tr)], np.int32)
+    R = oracle.sabsmax(K, bn)
+    Oe, Le, _ = oracle.exact(Q, K, V, bm, causal, blocks)
+    reduce = {3: lambda x: np.abs(x).max(0), 2: lambda x: x.mean(0),
+              0: lambda x: x[np.abs(x).argmax(0), np.arange(x.shape[1])]}
+    for mode in (0, 2, 3):
+        out = oracle.blocks(Q, K, V, bm, bn, causal, blocks, qrepr=oracle.sabsmax(Q, bm, mode))
+        for n, (b, h, i) in enumerate(blocks):
+            nr = min(bm, N - i * bm)
+            qs = reduce[mode](Q[0, h, i * bm:i * bm + nr].astype(np.float64))
+            j_hi = (i * bm + nr - 1) // bn if causal else -(-N // bn) - 1
+            seed = (R[0, h // 2, :j_hi + 1] @ qs).max() / math.sqrt(d)
+            assert np.abs(out["m_init"][n][:nr] - seed).max() < 1e-13
+            assert np.abs(out["O"][n][:nr] - Oe[n][:nr]).max() < 1e-12
+            assert np.abs(out["LSE"][n][:nr] - Le[n][:nr]).max() < 1e-12
+
+
 # ------------------------------------------------------------------ exactness identity
 CASES = [
     dict(N=96, d=8, bm=16, bn=16, causal=True, n_sink=1, n_local=1),
