@@ -118,9 +118,17 @@ int vsa_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LS
 
 /* VFA / VSA with the switches of the ablation study and of the sparse-attention variants
  * (Experiments: "Ablating the k_repr construction", "Removing m-initialization", "Ablating the
- * reordered schedule"; appendix: variants Blasst, Blasst_SWA, Blasst_Rowskip, Blasst_FA4).  As vfa_attn_fwd / vsa_attn_fwd,
+ * reordered schedule", "Replacing row-wise approximation with block-wise approximation on Q";
+ * appendix: variants Blasst, Blasst_SWA, Blasst_Rowskip, Blasst_FA4).  As vfa_attn_fwd / vsa_attn_fwd,
  * plus:
  *   repr_mode  block representation used when use_minit == 1 (see vfa_kblock_summary_mode)
+ *   q_repr_mode  0 = the approximate score uses each row of Q_i (the method); otherwise one summary
+ *              q_repr_i of the query block replaces its rows, the scalar q_repr_i . k_repr_j seeds every
+ *              row of the block alike: 1 = per-dimension largest magnitude of Q_i without its sign
+ *              ("absmax"), 2 = sabsmax(Q_i), 3 = per-dimension mean of Q_i (fp32 sum, rounded to bf16).
+ *              Needs use_minit == 1, and a workspace of vfa_workspace_bytes(B, Hkv, N, d, block_n) +
+ *              vfa_workspace_bytes(B, Hq, N, d, block_m) bytes: the query-block summaries
+ *              [B, Hq, ceil(N / block_m), d] are written behind the key-block summaries.
  *   reorder    1 = sink blocks, local blocks, then the rest (the method); 0 = ascending block
  *              order, the sink / local blocks keeping the exact-max update where they come
  *   freeze     1 = exact-max update on sink / local blocks only (the method); 0 = on every
@@ -130,15 +138,16 @@ int vsa_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LS
  *              suppressed (scores -inf, its state untouched); needs skipping and freeze = 0
  *   lazy_rescale_tau  >= 0 = Blasst_FA4: on kept tiles a row keeps its old max while the new one
  *              exceeds it by at most tau * ln 2; negative = off; needs skipping and freeze = 0
- * reorder = freeze = 1, repr_mode = 0, rowskip = 0, tau < 0 is exactly vfa_attn_fwd / vsa_attn_fwd.
+ * reorder = freeze = 1, repr_mode = q_repr_mode = 0, rowskip = 0, tau < 0 is exactly vfa_attn_fwd /
+ * vsa_attn_fwd.
  * Vanilla BLASST is (use_minit 0, reorder 0, freeze 0, threshold > 0); Blasst_SWA is the same with
  * reorder 1.
  * Every setting without skipping is exact attention; they differ in how far the frozen max sits
  * from the true one, which is what the ablation measures.  These run on the generic kernel. */
 int vfa_variant_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
                     int Hq, int Hkv, int N, int d, int block_m, int block_n, int causal,
-                    int n_sink, int n_local, int use_minit, int repr_mode, int reorder, int freeze,
-                    int rowskip, float lazy_rescale_tau, float softmax_scale,
+                    int n_sink, int n_local, int use_minit, int repr_mode, int q_repr_mode, int reorder,
+                    int freeze, int rowskip, float lazy_rescale_tau, float softmax_scale,
                     float skip_threshold_nats, unsigned char* skip_mask, void* workspace,
                     size_t workspace_bytes, void* stream);
 

@@ -40,7 +40,7 @@ def lib() -> ctypes.CDLL:
         L.vfa_kblock_summary_mode.restype = i
         L.vfa_kblock_summary_mode.argtypes = [vp, vp, i, i, i, i, i, i, vp]
         L.vfa_variant_fwd.restype = i
-        L.vfa_variant_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, i, i, i, i, i, i, f, f, f, vp, vp, sz, vp]
+        L.vfa_variant_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, i, i, i, i, i, i, i, f, f, f, vp, vp, sz, vp]
         L.vfa_kblock_summary_append.restype = i
         L.vfa_kblock_summary_append.argtypes = [vp, vp, i, i, i, i, i, i, i, vp]
         L.vfa_decode_workspace_bytes.restype = sz
@@ -205,20 +205,23 @@ def vsa_attn_fwd(Q, K, V, *, block_m=128, block_n=64, causal=True, n_sink=1, n_l
 
 
 def vfa_variant_fwd(Q, K, V, *, block_m=128, block_n=64, causal=True, n_sink=1, n_local=1, use_minit=True, repr_mode=0,
-                    reorder=True, freeze=True, rowskip=False, lazy_rescale_tau=-1.0, softmax_scale=0.0,
+                    q_repr_mode=0, reorder=True, freeze=True, rowskip=False, lazy_rescale_tau=-1.0, softmax_scale=0.0,
                     skip_threshold_nats=0.0, skip_mask=None,
                     workspace=None, out=None, lse=None, want_lse=True, stream=None):
     """VFA / VSA with the ablation switches; returns (O, LSE, mask) with mask None when nothing is skipped."""
     import torch
     B, Hq, Hkv, N, d = _check_qkv(Q, K, V)
     O, L = _outputs(Q, out, lse, want_lse)
+    if workspace is None and q_repr_mode:   # query-block summaries behind the key-block summaries
+        need = workspace_bytes(B, Hkv, N, d, block_n) + workspace_bytes(B, Hq, N, d, block_m)
+        workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
     ws, ws_bytes = _workspace(Q, K, block_n, workspace)
     M = skip_mask
     if M is None and skip_threshold_nats != 0.0:
         M = torch.empty((B, Hq, -(-N // block_m), -(-N // block_n)), dtype=torch.uint8, device=Q.device)
     rc = lib().vfa_variant_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(L), B, Hq, Hkv, N, d, block_m, block_n,
                                int(bool(causal)), int(n_sink), int(n_local), int(use_minit), int(repr_mode),
-                               int(bool(reorder)), int(bool(freeze)), int(bool(rowskip)), float(lazy_rescale_tau),
+                               int(q_repr_mode), int(bool(reorder)), int(bool(freeze)), int(bool(rowskip)), float(lazy_rescale_tau),
                                float(softmax_scale), float(skip_threshold_nats),
                                _ptr(M), _ptr(ws), ws_bytes, _stream(stream))
     if rc != 0:

@@ -55,8 +55,10 @@ struct Params {
     uint8_t* mask;
     int B, Hq, Hkv, N, Tr, Tc;
     int causal, n_sink, n_local, use_minit;
-    int pair_blocks;
-    int persist;      // ping-pong kernel: number of persistent workgroups (0 = one work item per workgroup)  // ping-pong kernel: the two wave groups take two adjacent query blocks of one head (else two heads)
+    const uint16_t* Qrepr;  // ablation: [B,Hq,Tr,D] one summary per query block replaces the rows of Q_i in the
+                            // approximate score (null = the row-wise method); generic kernel only
+    int pair_blocks;  // ping-pong kernel: the two wave groups take two adjacent query blocks of one head (else two heads)
+    int persist;      // ping-pong kernel: number of persistent workgroups (0 = one work item per workgroup)
     int order_asc;    // ablation: visit key blocks in ascending order (sink / local blocks keep the exact-max update)
     int all_special;  // ablation: exact-max update on every visited block
     int rowskip;      // skip variant: in a kept tile, rows that fail the threshold test are suppressed (generic kernel)
@@ -482,12 +484,22 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(const Params p) {
         const uint16_t* Rg = p.Krepr + ((size_t)(b * p.Hkv + hkv) * p.Tc) * D;
         float mx = -INFINITY;
         const int n_sum_tiles = (j_hi + BN) / BN;
+        // left operand: this lane's query row, or (block-wise ablation) the block's summary in every column,
+        // which gives all rows of the block the same seed
+        bf16x8 qm[KK];
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) qm[kk] = qf[kk];
+        if (p.Qrepr) {
+            const uint16_t* Qr = p.Qrepr + ((size_t)(b * p.Hq + h) * p.Tr + i) * D;
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) qm[kk] = *reinterpret_cast<const bf16x8*>(Qr + 16 * kk + 8 * hh);
+        }
         for (int ts = 0; ts < n_sum_tiles; ++ts) {
             __syncthreads();  // previous tile's readers are done
             load_tile<D, NW>(Rg, ts * BN, p.Tc, Ks, false, wave, lane);
             wait_vm0_and_sync();
             f32x16 st[2];
-            qk_tile<D>(Ks, qf, st, ql, hh);
+            qk_tile<D>(Ks, qm, st, ql, hh);
             mx = fmaxf(mx, tile_rowmax<true>(st, ts * BN, j_hi, hh));
         }
         m2 = xhalf_max(mx) * p.c;
@@ -1815,7 +1827,8 @@ int launch_fwd(const Params& p, int d, int block_m, hipStream_t s) {
     // adjacent query blocks; for VSA only where each block still meets its tiles in Alg. 2's order
     // (causal, at most one local block), since the skip decisions depend on the max at the time of the visit
     const bool head_pairs = (g & 1) == 0;
-    if (d == 128 && block_m == 128 && !p.order_asc && !p.all_special && !p.rowskip && !(MODE == MODE_VSA && p.tau2 >= 0.f) &&
+    if (d == 128 && block_m == 128 && !p.order_asc && !p.all_special && !p.rowskip && !p.Qrepr &&
+        !(MODE == MODE_VSA && p.tau2 >= 0.f) &&
         (head_pairs || MODE != MODE_VSA || (p.causal && p.n_local <= 1))) {
         static bool attr_set = false;  // opt in to more than 64 KB of LDS once per instantiation
         if (!attr_set) {
@@ -1868,12 +1881,13 @@ int vfa_vsa_common(int mode, const void* Q, const void* K, const void* V, void* 
                    int N, int d, int block_m, int block_n, int causal, int n_sink, int n_local, int use_minit,
                    float softmax_scale, float thr_nats, unsigned char* skip_mask, void* workspace,
                    size_t workspace_bytes, void* stream, int repr_mode = 0, int reorder = 1, int freeze = 1,
-                   int rowskip = 0, float lazy_tau = -1.f) {
+                   int rowskip = 0, float lazy_tau = -1.f, int q_repr_mode = 0) {
     int rc = check_common(Q, K, V, O, LSE, B, Hq, Hkv, N, d, block_m, block_n);
     if (rc != VFA_OK) return rc;
     if (n_sink < 0 || n_local < 0) return VFA_ERR_INVALID_ARG;
     if (!use_minit && n_sink + n_local == 0 && freeze) return VFA_ERR_INVALID_ARG;
     if (repr_mode < 0 || repr_mode > 3) return VFA_ERR_INVALID_ARG;
+    if (q_repr_mode < 0 || q_repr_mode > 3 || (q_repr_mode && use_minit != 1)) return VFA_ERR_INVALID_ARG;
     if (!(lazy_tau < 0.f) && !isfinite(lazy_tau)) return VFA_ERR_INVALID_ARG;   // negative = off; NaN / inf rejected
     if (lazy_tau != lazy_tau) return VFA_ERR_INVALID_ARG;
     if ((rowskip || lazy_tau >= 0.f) && (mode != MODE_VSA || freeze)) return VFA_ERR_INVALID_ARG;
@@ -1881,19 +1895,28 @@ int vfa_vsa_common(int mode, const void* Q, const void* K, const void* V, void* 
     if (!isfinite(softmax_scale)) return VFA_ERR_INVALID_ARG;
     if (use_minit < 0 || use_minit > 2) return VFA_ERR_INVALID_ARG;
     if (B == 0 || N == 0) return VFA_OK;
+    const size_t krepr_bytes = vfa_workspace_bytes(B, Hkv, N, d, block_n);
     if (use_minit) {
-        if (!workspace || !aligned16(workspace) || workspace_bytes < vfa_workspace_bytes(B, Hkv, N, d, block_n))
-            return VFA_ERR_INVALID_ARG;
-        if ((long long)B * Hkv > 65535) return VFA_ERR_UNSUPPORTED;
+        const size_t need = krepr_bytes + (q_repr_mode ? vfa_workspace_bytes(B, Hq, N, d, block_m) : 0);
+        if (!workspace || !aligned16(workspace) || workspace_bytes < need) return VFA_ERR_INVALID_ARG;
+        if ((long long)B * (q_repr_mode ? Hq : Hkv) > 65535) return VFA_ERR_UNSUPPORTED;
     }
     hipStream_t s = (hipStream_t)stream;
+    void* qrepr = nullptr;
     if (use_minit == 1) {
         rc = summary_launch(K, workspace, B, Hkv, N, d, block_n, repr_mode, s);
         if (rc != VFA_OK) return rc;
+        if (q_repr_mode) {  // the same reductions over the query blocks: 1 = unsigned absmax, 2 = sabsmax, 3 = mean
+            static const int kSummaryMode[4] = {0, 3, 0, 2};
+            qrepr = (char*)workspace + krepr_bytes;
+            rc = summary_launch(Q, qrepr, B, Hq, N, d, block_m, kSummaryMode[q_repr_mode], s);
+            if (rc != VFA_OK) return rc;
+        }
     }
     Params p{};
     p.Q = (const uint16_t*)Q; p.K = (const uint16_t*)K; p.V = (const uint16_t*)V;
     p.Krepr = (const uint16_t*)workspace; p.O = (uint16_t*)O; p.LSE = LSE; p.mask = skip_mask;
+    p.Qrepr = (const uint16_t*)qrepr;
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N; p.Tr = ceil_div(N, block_m); p.Tc = ceil_div(N, block_n);
     p.causal = causal ? 1 : 0; p.n_sink = n_sink; p.n_local = n_local; p.use_minit = use_minit ? 1 : 0;
     p.order_asc = reorder ? 0 : 1; p.all_special = freeze ? 0 : 1;
@@ -1990,13 +2013,14 @@ int vsa_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LS
 
 int vfa_variant_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq, int Hkv, int N,
                     int d, int block_m, int block_n, int causal, int n_sink, int n_local, int use_minit, int repr_mode,
-                    int reorder, int freeze, int rowskip, float lazy_rescale_tau, float softmax_scale,
+                    int q_repr_mode, int reorder, int freeze, int rowskip, float lazy_rescale_tau, float softmax_scale,
                     float skip_threshold_nats, unsigned char* skip_mask, void* workspace, size_t workspace_bytes,
                     void* stream) {
     const bool skipping = skip_threshold_nats != 0.f;
     return vfa_vsa_common(skipping ? MODE_VSA : MODE_VFA, Q, K, V, O, LSE, B, Hq, Hkv, N, d, block_m, block_n, causal,
                           n_sink, n_local, use_minit, softmax_scale, skip_threshold_nats, skipping ? skip_mask : nullptr,
-                          workspace, workspace_bytes, stream, repr_mode, reorder, freeze, rowskip, lazy_rescale_tau);
+                          workspace, workspace_bytes, stream, repr_mode, reorder, freeze, rowskip, lazy_rescale_tau,
+                          q_repr_mode);
 }
 
 int vfa_kblock_summary_append(const void* K, void* Krepr, int B, int Hkv, int n_cap, int n_old, int n_new, int d,

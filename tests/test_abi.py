@@ -76,13 +76,18 @@ def test_bad_arguments_are_rejected_before_launch(pkg):
     assert vs(*base, 1, 1, 1, 0.0, float("nan"), none, p, 1 << 20, none) == -1
     assert vs(*base, 1, 1, 1, 0.0, float("inf"), none, p, 1 << 20, none) == -1
     va = lambda *a: L.vfa_variant_fwd(*a)
-    assert va(*base, 1, 1, 1, 4, 1, 1, 0, -1.0, 0.0, 0.0, none, p, 1 << 20, none) == -1      # repr_mode out of range
-    assert va(*base, 0, 0, 0, 0, 1, 1, 0, -1.0, 0.0, 0.0, none, p, 1 << 20, none) == -1      # frozen max would stay -inf
-    assert va(*base, 1, 1, 1, 0, 0, 0, 0, -1.0, 0.0, -1.0, none, p, 1 << 20, none) == -1     # negative threshold
-    assert va(*base, 0, 0, 0, 0, 0, 0, 1, -1.0, 0.0, 0.0, none, p, 1 << 20, none) == -1      # row skip without a threshold
-    assert va(*base, 1, 1, 1, 0, 1, 1, 1, -1.0, 0.0, 4.0, none, p, 1 << 20, none) == -1      # row skip needs freeze = 0
-    assert va(*base, 0, 0, 0, 0, 0, 0, 0, float("nan"), 0.0, 4.0, none, p, 1 << 20, none) == -1
-    assert va(none, p, p, p, none, *ok_shape, 1, 1, 1, 0, 0, 0, 0, -1.0, 0.0, 0.0, none, p, 1 << 20, none) == -1
+    # after the shape: n_sink, n_local, use_minit, repr_mode, q_repr_mode, reorder, freeze, rowskip, tau, scale, threshold
+    assert va(*base, 1, 1, 1, 4, 0, 1, 1, 0, -1.0, 0.0, 0.0, none, p, 1 << 20, none) == -1      # repr_mode out of range
+    assert va(*base, 1, 1, 1, 0, 4, 1, 1, 0, -1.0, 0.0, 0.0, none, p, 1 << 20, none) == -1      # q_repr_mode out of range
+    assert va(*base, 1, 1, 0, 0, 1, 1, 1, 0, -1.0, 0.0, 0.0, none, p, 1 << 20, none) == -1      # q_repr without m-init
+    assert va(*base, 1, 1, 2, 0, 1, 1, 1, 0, -1.0, 0.0, 0.0, none, p, 1 << 20, none) == -1      # q_repr with caller's summaries
+    assert va(*base, 1, 1, 1, 0, 2, 1, 1, 0, -1.0, 0.0, 0.0, none, p, 2048, none) == -1         # room for k_repr only
+    assert va(*base, 0, 0, 0, 0, 0, 1, 1, 0, -1.0, 0.0, 0.0, none, p, 1 << 20, none) == -1      # frozen max would stay -inf
+    assert va(*base, 1, 1, 1, 0, 0, 0, 0, 0, -1.0, 0.0, -1.0, none, p, 1 << 20, none) == -1     # negative threshold
+    assert va(*base, 0, 0, 0, 0, 0, 0, 0, 1, -1.0, 0.0, 0.0, none, p, 1 << 20, none) == -1      # row skip without a threshold
+    assert va(*base, 1, 1, 1, 0, 0, 1, 1, 1, -1.0, 0.0, 4.0, none, p, 1 << 20, none) == -1      # row skip needs freeze = 0
+    assert va(*base, 0, 0, 0, 0, 0, 0, 0, 0, float("nan"), 0.0, 4.0, none, p, 1 << 20, none) == -1
+    assert va(none, p, p, p, none, *ok_shape, 1, 1, 1, 0, 0, 0, 0, 0, -1.0, 0.0, 0.0, none, p, 1 << 20, none) == -1
     ap = lambda *a: L.vfa_kblock_summary_append(*a)
     assert ap(p, p, 1, 1, 256, 10, 5, 128, 64, none) == -1                          # n_new < n_old
     assert ap(p, p, 1, 1, 256, 0, 300, 128, 64, none) == -1                         # beyond the capacity

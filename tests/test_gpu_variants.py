@@ -136,3 +136,73 @@ def test_rowskip_and_fa4_variants(vfa, oracle, sname, w, thr, vname, okw):
     # is compared at the ordinary bars, which a single flipped row of a tile that carries < lambda of the mass meets)
     stats = check_o_lse(O, L, ref["O"], ref["LSE"], blocks, w.block_m, w.N, vname + " vs oracle")
     print(sname, vname, stats, "counter %d of %d" % (ref["counters"][:, 2].sum(), ref["counters"][:, 0].sum()), flush=True)
+
+
+# ------------------------------------------------------------------ block-wise q_repr ablation
+# q_repr_mode of the library -> reduction of the oracle's summary routine (1 absmax without sign, 2 sabsmax, 3 mean)
+Q_SUMMARY = {1: 3, 2: 0, 3: 2}
+
+
+def _q_summaries(oracle, Qh, block_m, q_mode):
+    """Query-block summaries as the kernel holds them: elements of Q are exact in bf16, a mean is rounded once."""
+    qr = oracle.sabsmax(Qh, block_m, Q_SUMMARY[q_mode])
+    if q_mode == 3:
+        qr = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(qr.astype(np.float32))).astype(np.float64)
+    return qr
+
+
+@pytest.mark.parametrize("name,w", SHAPES, ids=[s[0] for s in SHAPES])
+@pytest.mark.parametrize("q_mode", [1, 2, 3])
+def test_blockwise_q_repr_is_exact_attention(vfa, oracle, name, w, q_mode):
+    import torch
+    t = wl.generate(w)
+    Q, K, V = gpu_inputs(t)
+    Qh, Kh, Vh = host_f32(t)
+    blocks = wl.all_blocks(w)
+    Oe, Le, Me = oracle.exact(Qh, Kh, Vh, w.block_m, w.causal, blocks)
+    O, L, M = vfa.vfa_variant_fwd(Q, K, V, block_m=w.block_m, block_n=w.block_n, causal=w.causal, n_sink=w.n_sink,
+                                  n_local=w.n_local, q_repr_mode=q_mode)
+    torch.cuda.synchronize()
+    assert M is None
+    ref = oracle.blocks(Qh, Kh, Vh, w.block_m, w.block_n, w.causal, blocks, n_sink=w.n_sink, n_local=w.n_local,
+                        qrepr=_q_summaries(oracle, Qh, w.block_m, q_mode))
+    tag = "q_repr_mode=%d" % q_mode
+    stats = check_o_lse(O, L, ref["O"], ref["LSE"], blocks, w.block_m, w.N, tag + " vs oracle")
+    check_o_lse(O, L, Oe, Le, blocks, w.block_m, w.N, tag + " vs exact")
+    gap = (Me - ref["m_final"])[~np.isnan(Me)]
+    print(name, tag, stats, "true max minus final max (nats): min %.2f max %.2f" % (gap.min(), gap.max()), flush=True)
+
+
+@pytest.mark.parametrize("sname,w,thr", SKIP_SHAPES, ids=[s[0] for s in SKIP_SHAPES])
+@pytest.mark.parametrize("q_mode", [1, 2, 3])
+@pytest.mark.parametrize("specials", [True, False], ids=["sink_local", "seed_only"])
+def test_blockwise_q_repr_skip_mask_bit_exact(vfa, oracle, sname, w, thr, q_mode, specials):
+    """The skip decisions depend on the frozen max, hence on the seed: the masks agree with the oracle's only if the
+    kernel seeds every row of a block with the block-wise score (and they differ from the row-wise method's).
+    Without sink and local blocks the seed alone is the frozen max, so every decision hangs on it."""
+    import torch
+    t = wl.generate(w)
+    Q, K, V = gpu_inputs(t)
+    Qh, Kh, Vh = host_f32(t)
+    blocks = wl.all_blocks(w)
+    n_sink, n_local = (w.n_sink, w.n_local) if specials else (0, 0)
+    kw = dict(block_m=w.block_m, block_n=w.block_n, causal=w.causal, n_sink=n_sink, n_local=n_local,
+              skip_threshold_nats=thr)
+    O, L, M = vfa.vfa_variant_fwd(Q, K, V, q_repr_mode=q_mode, **kw)
+    torch.cuda.synchronize()
+    okw = dict(n_sink=n_sink, n_local=n_local, vsa=True, skip_threshold_nats=thr)
+    ref = oracle.blocks(Qh, Kh, Vh, w.block_m, w.block_n, w.causal, blocks,
+                        qrepr=_q_summaries(oracle, Qh, w.block_m, q_mode), **okw)
+    got = M.cpu().numpy().reshape(len(blocks), w.Tc)
+    near = np.abs(ref["margin"]) < MASK_GUARD_NATS
+    assert near.sum() <= 2, "too many tiles on the threshold: pick another seed"
+    assert np.array_equal(got[~near], ref["mask"][~near]), (q_mode, int((got[~near] != ref["mask"][~near]).sum()))
+    rowwise = oracle.blocks(Qh, Kh, Vh, w.block_m, w.block_n, w.causal, blocks, **okw)
+    differ = int((rowwise["mask"] != ref["mask"]).sum())
+    if near.sum() == 0:
+        stats = check_o_lse(O, L, ref["O"], ref["LSE"], blocks, w.block_m, w.N, "q_repr skip vs oracle")
+    else:
+        stats = "output not compared: %d tile(s) within the guard band" % near.sum()
+    sparsity = (ref["mask"] == 1).sum() / max(1, (ref["mask"] != 2).sum())
+    print(sname, "q_repr_mode", q_mode, "specials", specials, "sparsity %.3f" % sparsity, "tiles decided differently from the row-wise seed:",
+          differ, stats, flush=True)
