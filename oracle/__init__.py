@@ -210,6 +210,31 @@ def e4m3_dequantize(codes, scale: float = 1.0):
     return out
 
 
+def mx_quantize(x, fmt: int = 0, pre_scale: float = 1.0):
+    """MX block quantisation along the last axis (32 elements per E8M0 scale): fmt 0 = E2M1 nibbles
+    (MXFP4, codes [..., d/2]), fmt 1 = E5M2 bytes (codes [..., d]); returns (codes, scales [..., d/32])."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    d = x.shape[-1]
+    rows = x.size // d
+    codes = np.zeros(x.shape[:-1] + ((d // 2) if fmt == 0 else d,), dtype=np.uint8)
+    scales = np.zeros(x.shape[:-1] + (d // 32,), dtype=np.uint8)
+    rc = _load().oracle_mx_quantize(_p(x, ctypes.c_float), ctypes.c_longlong(rows), d, ctypes.c_float(pre_scale), fmt,
+                                    _p(codes, ctypes.c_uint8), _p(scales, ctypes.c_uint8))
+    assert rc == 0
+    return codes, scales
+
+
+def mx_dequantize(codes, scales, fmt: int = 0):
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scales = np.ascontiguousarray(scales, dtype=np.uint8)
+    d = scales.shape[-1] * 32
+    out = np.empty(scales.shape[:-1] + (d,), dtype=np.float64)
+    rc = _load().oracle_mx_dequantize(_p(codes, ctypes.c_uint8), _p(scales, ctypes.c_uint8),
+                                      ctypes.c_longlong(out.size // d), d, fmt, _p(out, ctypes.c_double))
+    assert rc == 0
+    return out
+
+
 def decode(q, K, V, n_keys, block_n, *, n_sink=1, n_local=1, use_minit=True, n_parts=1, scale=None):
     """One query token per head against the first n_keys rows of a K/V cache [B,Hkv,n_cap,d].
     Returns dict O [B,Hq,d], LSE, m_init, m_final [B,Hq], l_parts [B,Hq,n_parts]."""

@@ -19,6 +19,10 @@
  *                     generalised as stated below.
  *   oracle_blocks     Alg. 1 (VFA), Alg. 2 (VSA) and the FA column of Table 1
  *                     (online softmax on every block), selected by switches.
+ *   oracle_e4m3_* / oracle_mx_*  the published FP8 and MX (E2M1 / E5M2 with shared E8M0 scales)
+ *                     codecs for the low-precision tensor regimes of the performance
+ *                     discussion; the attention itself is then checked on the
+ *                     dequantised operands with the functions above.
  *
  * Readings taken where the paper is silent or inconsistent (all 0-based here;
  * the paper counts blocks from 1):
@@ -614,5 +618,87 @@ int oracle_e4m3_quantize(const float *x, long long n, float inv_scale, uint8_t *
 
 int oracle_e4m3_dequantize(const uint8_t *codes, long long n, double scale, double *out) {
     for (long long i = 0; i < n; ++i) out[i] = e4m3_decode(codes[i]) * scale;
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Microscaling (MX) block formats for the 4-bit tensor regime of the performance discussion (the
+ * "C4" configurations): the published OCP MX layout, 32 consecutive elements along the feature
+ * axis share one E8M0 scale 2^(byte - 127); the elements are
+ *   fmt 0  E2M1 (bias 1, one mantissa bit: 0, 0.5, 1, 1.5, 2, 3, 4, 6 and their negatives), two
+ *          to a byte, element 2i in the low nibble of byte i;
+ *   fmt 1  E5M2 (bias 15, two mantissa bits, largest finite 57344), one to a byte; used for the
+ *          key-block summaries of E2M1 keys, whose entries carry different scales.
+ * Shared scale (the MX rule): byte = floor(log2(max|x|)) - emax + 127 with emax = 2 (E2M1) or 15
+ * (E5M2), clamped to [0, 254]; a block of zeros gets byte 0.  Elements: x / 2^(byte - 127) rounded
+ * to the nearest representable value, ties to the even mantissa, saturated at the largest finite
+ * value (the formats' infinities and NaNs are never produced).                                  */
+static unsigned minifloat_encode(double a, int mb, int bias, double maxv, unsigned maxcode) {
+    if (a >= maxv) return maxcode;
+    if (a < ldexp(1.0, 1 - bias))                          /* subnormal grid, step 2^(1 - bias - mb) */
+        return (unsigned)nearbyint(ldexp(a, mb - 1 + bias)); /* reaching 2^mb is the first normal code */
+    int e;
+    double f = frexp(a, &e);                               /* a = (2 f) 2^(e - 1), 2 f in [1, 2) */
+    int ex = e - 1;
+    double r = nearbyint((2.0 * f - 1.0) * (double)(1 << mb));
+    if (r == (double)(1 << mb)) { r = 0.0; ex += 1; }
+    unsigned code = ((unsigned)(ex + bias) << mb) | (unsigned)r;
+    return code > maxcode ? maxcode : code;
+}
+
+static double minifloat_decode(unsigned mag, int mb, int bias) {
+    const unsigned e = mag >> mb, m = mag & ((1u << mb) - 1u);
+    return e == 0 ? ldexp((double)m, 1 - bias - mb) : ldexp(1.0 + (double)m / (double)(1 << mb), (int)e - bias);
+}
+
+/* x [rows, d] float32, d a multiple of 32; y = x * pre_scale is taken in float32 (as the GPU
+ * pre-pass takes it).  codes: fmt 0 [rows, d/2], fmt 1 [rows, d]; scales [rows, d/32].       */
+int oracle_mx_quantize(const float *x, long long rows, int d, float pre_scale, int fmt,
+                       uint8_t *codes, uint8_t *scales) {
+    if (d <= 0 || d % 32 != 0 || (fmt != 0 && fmt != 1)) return -1;
+    const int mb = fmt ? 2 : 1, bias = fmt ? 15 : 1, emax = fmt ? 15 : 2, sbit = fmt ? 0x80 : 0x8;
+    const double maxv = fmt ? 57344.0 : 6.0;
+    const unsigned maxcode = fmt ? 0x7B : 0x7;
+    for (long long r = 0; r < rows; ++r)
+        for (int g = 0; g < d / 32; ++g) {
+            float y[32];
+            double amax = 0.0;
+            for (int t = 0; t < 32; ++t) {
+                y[t] = x[r * d + 32 * g + t] * pre_scale;
+                amax = fmax(amax, fabs((double)y[t]));
+            }
+            int byte = 0;
+            if (amax > 0.0) {
+                int e;
+                (void)frexp(amax, &e);                     /* floor(log2(amax)) = e - 1 */
+                byte = (e - 1) - emax + 127;
+                if (byte < 0) byte = 0;
+                if (byte > 254) byte = 254;
+            }
+            scales[r * (d / 32) + g] = (uint8_t)byte;
+            for (int t = 0; t < 32; ++t) {
+                const double v = ldexp((double)y[t], 127 - byte);
+                unsigned c = minifloat_encode(fabs(v), mb, bias, maxv, maxcode);
+                if (v < 0.0 || (v == 0.0 && signbit(v))) c |= (unsigned)sbit;
+                const long long idx = r * d + 32 * g + t;
+                if (fmt) codes[idx] = (uint8_t)c;
+                else if (idx & 1) codes[idx >> 1] |= (uint8_t)(c << 4);
+                else codes[idx >> 1] = (uint8_t)c;
+            }
+        }
+    return 0;
+}
+
+int oracle_mx_dequantize(const uint8_t *codes, const uint8_t *scales, long long rows, int d, int fmt,
+                         double *out) {
+    if (d <= 0 || d % 32 != 0 || (fmt != 0 && fmt != 1)) return -1;
+    for (long long r = 0; r < rows; ++r)
+        for (int t = 0; t < d; ++t) {
+            const long long idx = r * d + t;
+            const unsigned c = fmt ? codes[idx] : ((codes[idx >> 1] >> (4 * (idx & 1))) & 0xF);
+            const unsigned sbit = fmt ? 0x80 : 0x8;
+            const double v = minifloat_decode(c & (sbit - 1), fmt ? 2 : 1, fmt ? 15 : 1);
+            out[idx] = ldexp((c & sbit) ? -v : v, (int)scales[r * (d / 32) + t / 32] - 127);
+        }
     return 0;
 }

@@ -673,6 +673,105 @@ def test_e4m3_codec_against_the_format_definition():
     assert np.all(np.diff(orc.e4m3_dequantize(orc.e4m3_quantize(np.sort(x), 16.0))) >= 0)      # monotone
 
 
+E2M1_VALUES = [0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0]    # the format's table, codes 0..7; 8..15 are their negatives
+
+
+def _nearest_on_grid(y, grid):
+    """Index of the grid value nearest to y; of two equally near ones, the even index (the codes of a
+    small float are consecutive integers, so an even code is an even mantissa); beyond the grid: its end."""
+    grid = np.asarray(grid)
+    dist = np.abs(grid[None, :] - np.abs(y)[:, None])
+    best = dist.min(1)
+    out = np.empty(len(y), int)
+    for n in range(len(y)):
+        cand = np.flatnonzero(dist[n] == best[n])
+        out[n] = cand[0] if len(cand) == 1 else [c for c in cand if c % 2 == 0][0]
+    return out
+
+
+def test_mx_codecs_against_the_format_definitions(oracle):
+    """E2M1 decode = the published table; E5M2 decode = the top byte of an IEEE half (library: numpy float16);
+    encode = nearest table entry, ties to the even code, checked by brute force over the decoded tables on
+    random values, on every midpoint between neighbours and beyond the largest finite value."""
+    one = np.full((1, 1), 127, np.uint8)                       # scale 2^0
+    nib = np.zeros((16, 16), np.uint8)
+    nib[:, 0] = np.arange(16)                                  # code c in element 0 of row c, zeros elsewhere
+    dec = oracle.mx_dequantize(nib, np.repeat(one, 16, 0), fmt=0)
+    assert np.array_equal(dec[:, 0], E2M1_VALUES + [-v for v in E2M1_VALUES]) and np.all(dec[:, 1:] == 0)
+    hi = np.zeros((16, 16), np.uint8)
+    hi[:, 3] = np.arange(16) << 4                              # high nibble of byte 3 is element 7
+    assert np.array_equal(oracle.mx_dequantize(hi, np.repeat(one, 16, 0), fmt=0)[:, 7], dec[:, 0])
+    finite = np.array([c for c in range(256) if (c & 0x7C) != 0x7C], np.uint8)
+    rows = np.zeros((len(finite), 32), np.uint8)
+    rows[:, 5] = finite
+    dec5 = oracle.mx_dequantize(rows, np.repeat(one, len(finite), 0), fmt=1)[:, 5]
+    half = (finite.astype(np.uint16) << 8).view(np.float16).astype(np.float64)
+    assert np.array_equal(dec5, half)
+    rng = np.random.default_rng(90)
+    for fmt, grid in ((0, np.array(E2M1_VALUES)), (1, half[:len(half) // 2])):   # non-negative half of each table
+        assert np.all(np.diff(grid) > 0)
+        mids = (grid[1:] + grid[:-1]) / 2
+        top = grid[-1]
+        # keep the block maximum in [top/2 .. top] * (1 + something < 1) so that the shared scale is 2^0:
+        # element 0 of every row carries `top`, the value under test sits in element 1
+        ys = np.concatenate([mids, grid, rng.uniform(0, top * 1.3, 400), [top * 1.01, top * 1.29]])
+        ys = ys[ys < top * 4 / 3] if fmt == 0 else ys[ys < 65536]
+        x = np.zeros((len(ys), 32), np.float32)
+        x[:, 0] = top
+        x[:, 1] = ys * np.where(np.arange(len(ys)) % 2 == 0, 1, -1)
+        ys = np.abs(x[:, 1].astype(np.float64))                 # what float32 kept of them
+        codes, scales = oracle.mx_quantize(x, fmt)
+        assert np.all(scales == 127)
+        got = (codes[:, 0] >> 4) if fmt == 0 else codes[:, 1]
+        sign = got & (0x8 if fmt == 0 else 0x80)
+        assert np.array_equal(sign != 0, np.signbit(x[:, 1]))      # -0 keeps its sign bit
+        assert np.array_equal(got & (0x7 if fmt == 0 else 0x7F), _nearest_on_grid(ys, grid))
+
+
+def test_mx_shared_scale_rule_hand_values(oracle):
+    """byte = floor(log2(max|x|)) - emax + 127: E2M1 (emax 2): max 6 -> 127, 7.9 -> 127 (7.9 saturates to 6),
+    8 -> 128 (8 / 2 = 4), 0.3 -> 123 (0.3 * 16 = 4.8 -> 4); E5M2 (emax 15): max 6 -> 114; zeros -> byte 0."""
+    x = np.zeros((6, 64), np.float32)
+    x[0, 0], x[1, 1], x[2, 2], x[3, 3] = 6.0, -7.9, 8.0, 0.3
+    x[4, 40] = 6.0                                             # second block of the row; its first block is all zero
+    x[0, 1], x[2, 3] = 1.2, 3.1                                # 1.2 -> 1.0;  3.1 / 2 = 1.55 -> 1.5
+    codes, scales = oracle.mx_quantize(x, 0)
+    assert scales.tolist() == [[127, 0], [127, 0], [128, 0], [123, 0], [0, 127], [0, 0]]
+    back = oracle.mx_dequantize(codes, scales, 0)
+    want = np.zeros((6, 64))
+    want[0, 0], want[1, 1], want[2, 2], want[3, 3], want[4, 40] = 6.0, -6.0, 8.0, 0.25, 6.0
+    want[0, 1], want[2, 3] = 1.0, 3.0
+    assert np.array_equal(back, want)
+    codes5, scales5 = oracle.mx_quantize(x, 1)
+    assert scales5[0, 0] == 114 and scales5[3, 0] == 110 and scales5[5].tolist() == [0, 0]
+    back5 = oracle.mx_dequantize(codes5, scales5, 1)
+    # two mantissa bits: the top binade of a block holds 4, 5, 6, 7 (times its scale), so a block maximum of 7.9
+    # saturates to 7; 1.2 -> 1.25 and 3.1 -> 3 are ordinary roundings
+    assert back5[0, 0] == 6.0 and back5[1, 1] == -7.0 and back5[2, 2] == 8.0 and back5[0, 1] == 1.25 and back5[2, 3] == 3.0
+    # pre_scale multiplies in float32 before anything else
+    c2, s2 = oracle.mx_quantize(x, 0, pre_scale=0.5)
+    assert np.array_equal(oracle.mx_dequantize(c2, s2, 0), oracle.mx_dequantize(*oracle.mx_quantize(x * np.float32(0.5), 0), 0))
+    assert s2[2, 0] == 127
+
+
+def test_mx_round_trip_properties(oracle):
+    """Values already on a block's grid survive the round trip; any value moves by at most a quarter of the block
+    maximum (E2M1: half a step of 2 at the top binade, or the saturation of [6, 8) to 6)."""
+    rng = np.random.default_rng(91)
+    x = (rng.standard_normal((50, 128)) * np.exp(rng.standard_normal((50, 1)) * 3)).astype(np.float32)
+    codes, scales = oracle.mx_quantize(x, 0)
+    back = oracle.mx_dequantize(codes, scales, 0)
+    amax = np.abs(x.astype(np.float64)).reshape(50, 4, 32).max(2, keepdims=True)
+    assert np.all(np.abs(back.reshape(50, 4, 32) - x.reshape(50, 4, 32)) <= amax / 4 * (1 + 1e-12))
+    c2, s2 = oracle.mx_quantize(back.astype(np.float32), 0)
+    assert np.array_equal(oracle.mx_dequantize(c2, s2, 0), back)
+    # E5M2 summaries of E2M1-valued vectors whose entries come from different scales are exact over 29 binades
+    mixed = back.reshape(50, 4, 32) * np.exp2(rng.integers(-12, 1, (50, 4, 32)))
+    mixed = mixed.reshape(50, 128).astype(np.float32)
+    c5, s5 = oracle.mx_quantize(mixed, 1)
+    assert np.array_equal(oracle.mx_dequantize(c5, s5, 1), mixed.astype(np.float64))
+
+
 def test_bf16_rounding_is_nearest_even():
     x = np.array([1.0, 1.00390625, 1.01171875, -1.00390625, 3.4e38, 1e-40, 0.0], np.float32)
     bits = wl.f32_to_bf16_bits(x)
