@@ -108,7 +108,7 @@ def main():
     ap.add_argument("--seed", type=int, default=wl.DEFAULT_SEED)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=3500, help="random query blocks in the oracle timing sample")
-    ap.add_argument("--only", default="", help="comma list of fa,vfa,vsa,summary,decode,fp8 to time (default all)")
+    ap.add_argument("--only", default="", help="comma list of fa,vfa,vsa,summary,decode,fp8,mxfp4 to time (default all; mxfp4 needs fp8)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is a single-GPU kernel path; run it with --gpus 1 "
@@ -128,7 +128,7 @@ def main():
     M = torch.empty((w.B, w.Hq, w.Tr, w.Tc), dtype=torch.uint8, device=dev)
     kw = dict(block_m=w.block_m, block_n=w.block_n, causal=w.causal, out=O, lse=L)
     vkw = dict(n_sink=w.n_sink, n_local=w.n_local, workspace=ws, **kw)
-    only = set(filter(None, args.only.split(","))) or {"fa", "vfa", "vsa", "summary", "decode", "fp8"}
+    only = set(filter(None, args.only.split(","))) or {"fa", "vfa", "vsa", "summary", "decode", "fp8", "mxfp4"}
 
     def run_vfa():
         vfa.vfa_attn_fwd(Q, K, V, use_minit=1, **vkw)
@@ -221,6 +221,27 @@ def main():
                       "kernel": "attn_fp8_kernel (4 waves, no ping-pong scheduling); vfa: scale folded into the MFMA, "
                                 "frozen max into the accumulator start; vfa_unfolded: the same operands' plain path"}
         del Q8f
+        if "mxfp4" in only:
+            # the 4-bit tensor regime for the scores (MXFP4 Q and K, E4M3 V): peak for a mix of one 4-bit and one
+            # 8-bit product of equal size = 2 / (1 / 10.1 + 1 / 5.0) PFLOP/s
+            pre = float(np.float32(w.scale) * np.float32(math.log2(math.e)))
+            Q4, QS = vfa.mxfp4_quantize(Q)
+            Q4f, QSf = vfa.mxfp4_quantize(Q, pre)
+            K4, KS = vfa.mxfp4_quantize(K)
+            ws4 = torch.empty(vfa.mxfp4_workspace_bytes(w.B, w.Hkv, w.N), dtype=torch.uint8, device=dev)
+            m4 = dict(descale_v=sv, block_m=w.block_m, block_n=w.block_n, causal=w.causal, n_sink=w.n_sink,
+                      n_local=w.n_local, workspace=ws4, out=O, lse=L)
+            ms4_fa = time_region(lambda: vfa.mxfp4_attn_fwd(Q4, QS, K4, KS, Vt8, frozen=False, **m4), args.steps, args.warmup)
+            ms4_plain = time_region(lambda: vfa.mxfp4_attn_fwd(Q4, QS, K4, KS, Vt8, frozen=True, **m4), args.steps, args.warmup)
+            ms4_vfa = time_region(lambda: vfa.mxfp4_attn_fwd(Q4f, QSf, K4, KS, Vt8, frozen=True, softmax_scale=math.log(2.0), **m4),
+                                  args.steps, args.warmup)
+            peak4 = 2.0 / (1.0 / 10100.0 + 1.0 / 5000.0)
+            out["mxfp4"] = {"vfa_ms": ms4_vfa, "vfa_tflops": dense / ms4_vfa / 1e9, "fa_ms": ms4_fa, "fa_tflops": dense / ms4_fa / 1e9,
+                            "speedup_vfa_vs_fa": ms4_fa / ms4_vfa, "peak_tflops": peak4, "frac_vfa": dense / ms4_vfa / 1e9 / peak4,
+                            "vfa_unfolded_ms": ms4_plain, "vfa_unfolded_tflops": dense / ms4_plain / 1e9,
+                            "kernel": "attn_mx4_kernel (Q.K^T on MXFP4, P.V on 8-bit operands; 4 waves); vfa: Q multiplied by "
+                                      "scale * log2(e) before quantising, frozen max into the accumulator start"}
+            del Q4, QS, Q4f, QSf, K4, KS, ws4
         del Q8, K8, Vt8, ws8
     if "decode" in only:
         out["decode"] = decode_step(args, torch, vfa)

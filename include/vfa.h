@@ -232,6 +232,37 @@ int vfa_fp8_attn_fwd(int frozen, const void* Q8, const void* K8, const void* Vt8
                      float descale_k, float descale_v, void* workspace, size_t workspace_bytes,
                      void* stream);
 
+/* ---- MXFP4 scores: the 4-bit tensor regime of the performance discussion (the "C4" configurations):
+ * Q.K^T on operands in the published MX block format (E2M1 elements, two to a byte with the even
+ * element in the low nibble, and one E8M0 scale byte 2^(byte - 127) per 32 consecutive features);
+ * P.V as in the FP8 path (exp(S - m) and V in E4M3), softmax arithmetic in fp32.  The paper gives no
+ * quantisation scheme; this is the MX one.  Only d = 128 with 128x64 blocks. ---- */
+
+/* X (bf16, n elements, n a multiple of 32, 16-byte aligned; blocks of 32 never straddle rows when d is a
+ * multiple of 32) -> X4 (n/2 bytes) and XS (n/32 scale bytes).  y = x * pre_scale in fp32; scale byte =
+ * floor(log2(max|y| of the block)) - 2 + 127, at least 0 (an all-zero block gets 0); element = y / scale
+ * rounded to the nearest of 0, 0.5, 1, 1.5, 2, 3, 4, 6, ties to the even mantissa, saturated at 6. */
+int vfa_mxfp4_quantize(const void* X, void* X4, void* XS, long long n, float pre_scale, void* stream);
+
+/* Bytes of workspace of vfa_mxfp4_attn_fwd (the key-block summaries), 0 for invalid arguments. */
+size_t vfa_mxfp4_workspace_bytes(int B, int Hkv, int N);
+
+/* Attention forward with MXFP4 scores.  Q4 [B, Hq, N, 64] and QS [B, Hq, N, 4], K4 [B, Hkv, N, 64] and
+ * KS [B, Hkv, N, 4] from vfa_mxfp4_quantize (scale arrays 4-byte aligned); Vt8 from vfa_fp8_pack_v with
+ * its descale_v.  Scores are (dequantised Q) . (dequantised K) * softmax_scale.  frozen = 0: online softmax
+ * on every block; frozen = 1: Alg. 1, the summaries being the sabsmax of the dequantised keys held as MX
+ * blocks of E5M2 elements (use_minit = 1 computes them into the workspace: [B, Hkv, Tc, 128] codes followed
+ * by [B, Hkv, Tc, 4] scale bytes; 2 = the workspace already holds them).  exp(S - m), l, O and LSE as in
+ * vfa_fp8_attn_fwd.  With frozen = 1 and softmax_scale * log2(e) = 1 (to 2^-18: the caller multiplied Q by
+ * its scale * log2(e) before quantising and passes softmax_scale = ln 2) the frozen max enters as the start
+ * value of the matrix instruction's accumulators and no per-score arithmetic but exp is left.
+ * Errors as vfa_fp8_attn_fwd. */
+int vfa_mxfp4_attn_fwd(int frozen, const void* Q4, const void* QS, const void* K4, const void* KS,
+                       const void* Vt8, void* O, float* LSE, int B, int Hq, int Hkv, int N, int d,
+                       int block_m, int block_n, int causal, int n_sink, int n_local, int use_minit,
+                       float softmax_scale, float descale_v, void* workspace, size_t workspace_bytes,
+                       void* stream);
+
 /* Static string for a return code. */
 const char* vfa_strerror(int code);
 

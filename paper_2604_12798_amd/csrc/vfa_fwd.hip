@@ -1475,6 +1475,8 @@ __device__ __forceinline__ void qk_tile8(const uint8_t* kt, const i32x8* qf, f32
         st[e >> 1] = mfma_f8(f[e], qf[e & 1], (e & 1) ? st[e >> 1] : (start ? *start : f32x16{0}), scale_a);
 }
 
+// P_BF8: the P operand holds E5M2 codes (V stays E4M3)
+template <bool P_BF8 = false>
 __device__ __forceinline__ void pv_tile8(const uint8_t* vt, const uint32_t* pk, f32x16* ot, int lane, int hh) {
     const i32x8 pf = {(int)pk[0], (int)pk[1], (int)pk[2], (int)pk[3], (int)pk[4], (int)pk[5], (int)pk[6], (int)pk[7]};
     i32x8 f[4];
@@ -1484,12 +1486,29 @@ __device__ __forceinline__ void pv_tile8(const uint8_t* vt, const uint32_t* pk, 
         f[db] = lds_frag8(vt + Tile8::v_off(row, 2 * hh), vt + Tile8::v_off(row, 2 * hh + 1));
     }
 #pragma unroll
-    for (int db = 0; db < 4; ++db) ot[db] = mfma_f8(f[db], pf, ot[db]);
+    for (int db = 0; db < 4; ++db)
+        ot[db] = P_BF8 ? __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[db], pf, ot[db], 0, 1, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f)
+                       : mfma_f8(f[db], pf, ot[db]);
+}
+
+// four values in [0, 1] -> one dword of 8-bit codes: E4M3 of q * 2^8, or (P_BF8) E5M2 of q * 2^15, which trades one
+// mantissa bit for 14 more binades below 1: for a frozen max that may sit far above the scores
+template <bool P_BF8>
+__device__ __forceinline__ uint32_t pack_p8(const float* q) {
+    s16x2 w = {0, 0};
+    if (P_BF8) {
+        w = __builtin_amdgcn_cvt_scalef32_pk_bf8_f32(w, q[0], q[1], 0x1p-15f, false);
+        w = __builtin_amdgcn_cvt_scalef32_pk_bf8_f32(w, q[2], q[3], 0x1p-15f, true);
+    } else {
+        w = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(w, q[0], q[1], 0.00390625f, false);  // / 2^-8
+        w = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(w, q[2], q[3], 0.00390625f, true);
+    }
+    return __builtin_bit_cast(uint32_t, w);
 }
 
 // softmax step with E4M3 output: as softmax_tile, but q = min(exp2(s c - m - H), 1) (clamp modifier of the
 // exponential), lsum += q, and four q's go to one dword as q * 2^8 (pk[0..7] = the B operand of P.V)
-template <bool SPECIAL, bool MASKED>
+template <bool SPECIAL, bool MASKED, bool P_BF8 = false>
 __device__ __forceinline__ void softmax_tile8(f32x16* st, uint32_t* pk, f32x16* ot, float& m2, float& lsum, float c,
                                               float headroom, int key0, int limit, int hh) {
     if (MASKED) {
@@ -1521,17 +1540,14 @@ __device__ __forceinline__ void softmax_tile8(f32x16* st, uint32_t* pk, f32x16* 
                 q[e] = __builtin_amdgcn_fmed3f(__builtin_amdgcn_exp2f(__builtin_fmaf(st[t][r + e], c, -sub)), 0.f, 1.f);
                 lsum += q[e];
             }
-            s16x2 w = {0, 0};
-            w = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(w, q[0], q[1], 0.00390625f, false);  // / 2^-8
-            w = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(w, q[2], q[3], 0.00390625f, true);
-            pk[4 * t + (r >> 2)] = __builtin_bit_cast(uint32_t, w);
+            pk[4 * t + (r >> 2)] = pack_p8<P_BF8>(q);
         }
 }
 
 // The same for a frozen tile when the scores arrive as s c - m - H already (scale folded into the MFMA, the
 // rest into its accumulator start): exp, sum, convert.  Nothing per score is left of the scaling and the
 // subtraction, which the exact-max path cannot avoid because its m depends on the very tile.
-template <bool MASKED>
+template <bool MASKED, bool P_BF8 = false>
 __device__ __forceinline__ void softmax_tile8_folded(f32x16* st, uint32_t* pk, float& lsum, int key0, int limit, int hh) {
     if (MASKED) {
         const int rel = limit - key0 - 4 * hh;
@@ -1550,10 +1566,7 @@ __device__ __forceinline__ void softmax_tile8_folded(f32x16* st, uint32_t* pk, f
                 q[e] = __builtin_amdgcn_fmed3f(__builtin_amdgcn_exp2f(st[t][r + e]), 0.f, 1.f);
                 lsum += q[e];
             }
-            s16x2 w = {0, 0};
-            w = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(w, q[0], q[1], 0.00390625f, false);
-            w = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(w, q[2], q[3], 0.00390625f, true);
-            pk[4 * t + (r >> 2)] = __builtin_bit_cast(uint32_t, w);
+            pk[4 * t + (r >> 2)] = pack_p8<P_BF8>(q);
         }
 }
 
@@ -1784,6 +1797,343 @@ __global__ __launch_bounds__(128) void fp8_kblock_summary_kernel(const uint8_t* 
         best = mx > mb ? x : (mb > mx ? best : min(best, x));
     }
     R[((size_t)bh * Tc + j) * 128 + t] = (uint8_t)best;
+}
+
+// ---------------------------------------------------------------------------------------------
+// MXFP4 scores: the 4-bit tensor regime (Q.K^T on E2M1 elements with one E8M0 scale per 32 features, the
+// published MX block format; P.V stays on E4M3 as above, since exp(S - m) in [0, 1] needs more than the one
+// mantissa bit of E2M1).  v_mfma_scale_f32_32x32x64_f8f6f4 with both operands E2M1 runs a 64-deep step in
+// 32 cycles, twice the E4M3 rate, and takes the block scales as operands: lane (row, half hh) supplies the
+// scale byte of its own 32 elements, k = 32 hh .. 32 hh + 31 of the step, which are features
+// 64 kh + 32 hh .. + 31: exactly one MX block.  The scale byte is replicated into all four bytes of its
+// register, so the byte select of the instruction does not matter.
+// Key-block summaries of MXFP4 keys are not MXFP4 vectors (their entries come from keys with different
+// scales): they are kept as MX blocks of E5M2 elements (two mantissa bits cover the one of E2M1, and the 29
+// binades below the block maximum cover the spread of the keys' scales), and the m-initialisation multiplies
+// them with the E2M1 queries in the same instruction (A = E5M2, B = E2M1).  Measured for that mixed form: the
+// k index of an element is 32 hh + j for nibble j of a 4-bit operand, but 16 hh + j (j < 16) or
+// 32 + 16 hh + (j - 16) for byte j of an 8-bit operand, and the scale of lane half b covers k = 32 b .. 32 b + 31
+// in both (for 8-bit data: bytes 16 b .. 16 b + 15 of BOTH halves).  Two operands of equal width pair up whatever
+// the order, which is all the paths above need; here the summary's 16-byte chunks are picked to match.
+struct Tile4 {
+    static constexpr int KBYTES = BN * 64;  // K tile: 64 rows of 64 bytes (128 nibbles)
+    // 16-byte chunk c (0..3) of row r sits at chunk position c ^ ((r >> 2) & 3): 16 consecutive rows reading one
+    // logical chunk cover all 64 banks
+    __device__ static int k_off(int r, int c) { return r * 64 + ((c ^ ((r >> 2) & 3)) << 4); }
+};
+
+// E2M1 magnitudes by code (sign in bit 3)
+__device__ __forceinline__ float e2m1_value(uint32_t code) {
+    const uint32_t mag = code & 7u;
+    const float v = mag < 2u ? 0.5f * (float)mag : __builtin_ldexpf(1.0f + 0.5f * (float)(mag & 1u), (int)(mag >> 1) - 1);
+    return (code & 8u) ? -v : v;
+}
+
+// X bf16 -> MXFP4: thread = 8 consecutive elements, 4 threads = one block of 32.  y = x * pre_scale (fp32);
+// scale byte = exponent field of max|y| - 2, at least 0; element = y / 2^(byte - 127) rounded to the nearest
+// of 0, 0.5, 1, 1.5, 2, 3, 4, 6, ties to the even mantissa (the comparisons below), saturated at 6.
+__global__ __launch_bounds__(256) void mx4_quantize_kernel(const uint16_t* __restrict__ X, uint8_t* __restrict__ Y,
+                                                           uint8_t* __restrict__ S, long long n8, float pre_scale) {
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    const bool live = i < n8;  // (n8 is a multiple of 4, so the four threads of a block are live together)
+    u32x4 x = {0, 0, 0, 0};
+    if (live) x = *reinterpret_cast<const u32x4*>(X + i * 8);
+    float v[8];
+    float amax = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        v[2 * e] = __uint_as_float(x[e] << 16) * pre_scale;
+        v[2 * e + 1] = __uint_as_float(x[e] & 0xffff0000u) * pre_scale;
+        amax = fmaxf(amax, fmaxf(fabsf(v[2 * e]), fabsf(v[2 * e + 1])));
+    }
+    amax = fmaxf(amax, __shfl_xor(amax, 1));
+    amax = fmaxf(amax, __shfl_xor(amax, 2));
+    const int ef = (int)((__float_as_uint(amax) >> 23) & 0xffu);
+    const int sb = max(ef - 2, 0);
+    const float mult = __uint_as_float((uint32_t)(254 - sb) << 23);  // 2^(127 - sb)
+    uint32_t w = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float y = fabsf(v[e]) * mult;
+        uint32_t c = (uint32_t)(y > 0.25f) + (uint32_t)(y >= 0.75f) + (uint32_t)(y > 1.25f) + (uint32_t)(y >= 1.75f) +
+                     (uint32_t)(y > 2.5f) + (uint32_t)(y >= 3.5f) + (uint32_t)(y > 5.0f);
+        c |= (__float_as_uint(v[e]) >> 28) & 8u;
+        w |= c << (4 * e);
+    }
+    if (live) {
+        *reinterpret_cast<uint32_t*>(Y + i * 4) = w;
+        if ((threadIdx.x & 3) == 0) S[i >> 2] = (uint8_t)sb;
+    }
+}
+
+// sabsmax of a block of MXFP4 keys, per feature over the dequantised values (tie -> the positive one), stored
+// as MX blocks of E5M2: scale byte = exponent field of the block maximum - 15; codes [B*Hkv, Tc, 128],
+// scales [B*Hkv, Tc, 4].  One thread per feature.
+__global__ __launch_bounds__(128) void mx4_kblock_summary_kernel(const uint8_t* __restrict__ K4, const uint8_t* __restrict__ KS,
+                                                                 uint8_t* __restrict__ R, uint8_t* __restrict__ RS, int N,
+                                                                 int Tc) {
+    const int j = blockIdx.x, bh = blockIdx.y, t = threadIdx.x;
+    const int rows = min(BN, N - j * BN);
+    const uint8_t* kc = K4 + ((size_t)bh * N + (size_t)j * BN) * 64 + (t >> 1);
+    const uint8_t* ks = KS + ((size_t)bh * N + (size_t)j * BN) * 4 + (t >> 5);
+    float best = 0.f;
+    for (int r = 0; r < rows; ++r) {
+        const uint32_t code = ((uint32_t)kc[(size_t)r * 64] >> (4 * (t & 1))) & 0xfu;
+        const float v = __builtin_ldexpf(e2m1_value(code), (int)ks[(size_t)r * 4] - 127);
+        const float av = fabsf(v), ab = fabsf(best);
+        best = (r == 0 || av > ab || (av == ab && v > best)) ? v : best;
+    }
+    best = best == 0.f ? 0.f : best;  // a column of zeros of either sign: +0
+    float amax = fabsf(best);
+#pragma unroll
+    for (int o = 16; o >= 1; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));  // the 32 features of one MX block
+    const int ef = (int)((__float_as_uint(amax) >> 23) & 0xffu);
+    const int sb = max(ef - 15, 0);
+    const float y = __builtin_ldexpf(best, 127 - sb);  // at most 1.5 * 2^15: inside E5M2's finite range
+    R[((size_t)bh * Tc + j) * 128 + t] = (uint8_t)(__builtin_amdgcn_cvt_pk_bf8_f32(y, 0.f, 0, false) & 0xff);
+    if ((t & 31) == 0) RS[((size_t)bh * Tc + j) * 4 + (t >> 5)] = (uint8_t)sb;
+}
+
+__device__ __forceinline__ f32x16 mfma_f4(const u32x4& a, const u32x4& b, const f32x16& c, int scale_a, int scale_b) {
+    const i32x8 av = {(int)a[0], (int)a[1], (int)a[2], (int)a[3], 0, 0, 0, 0};
+    const i32x8 bv = {(int)b[0], (int)b[1], (int)b[2], (int)b[3], 0, 0, 0, 0};
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, bv, c, 4, 4, 0, scale_a, 0, scale_b);
+}
+__device__ __forceinline__ f32x16 mfma_bf8_f4(const i32x8& a, const u32x4& b, const f32x16& c, int scale_a, int scale_b) {
+    const i32x8 bv = {(int)b[0], (int)b[1], (int)b[2], (int)b[3], 0, 0, 0, 0};
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, bv, c, 1, 4, 0, scale_a, 0, scale_b);
+}
+
+// byte n (0..3, per lane) of x in all four bytes
+__device__ __forceinline__ int spread_byte(uint32_t x, uint32_t n) {
+    return (int)__builtin_amdgcn_perm(x, x, n * 0x01010101u);
+}
+
+// 64 dwords (the four scale bytes of rows first_row .. first_row + 63 of a row-major [*, 4] array, rows clamped
+// to row_limit - 1) -> LDS, by one wave
+__device__ __forceinline__ void load_scales64(const uint8_t* base, int first_row, int row_limit, uint32_t* dst, int lane) {
+    const uint8_t* src = base + (size_t)min(first_row + lane, row_limit - 1) * 4;
+    const uint32_t lds_addr =
+        __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t*)dst);
+    uint32_t m0_save;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %2, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(m0_save)
+                 : "s"(lds_addr), "v"(src)
+                 : "memory");
+}
+
+// MXFP4 K tile (64 rows of 64 bytes from a row-major [*, 64] array, rows clamped) -> LDS: four one-KiB pieces,
+// one per wave
+__device__ __forceinline__ void load_tile4(const uint8_t* base, int first_row, int row_limit, uint8_t* dst, int wave,
+                                           int lane) {
+    const int r = 16 * wave + (lane >> 2);
+    const int c = (lane & 3) ^ ((r >> 2) & 3);
+    const uint8_t* src = base + (size_t)min(first_row + r, row_limit - 1) * 64 + c * 16;
+    const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
+        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)(dst + wave * 1024));
+    uint32_t m0_save;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(m0_save)
+                 : "s"(lds_addr), "v"(src)
+                 : "memory");
+}
+
+// S^T tile from an MXFP4 K tile and its scales: st[t][i] as in qk_tile, in units of the dequantised products
+// (the block scales are applied inside the instruction), plus *start if given
+__device__ __forceinline__ void qk_tile4(const uint8_t* kt, const uint32_t* ksc, const u32x4* qf, const int* qs, f32x16* st,
+                                         int ql, int hh, const f32x16* start = nullptr) {
+    u32x4 f[4];
+    uint32_t sc[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) sc[t] = ksc[32 * t + ql];
+#pragma unroll
+    for (int e = 0; e < 4; ++e)  // e = 2 t + kh
+        f[e] = *reinterpret_cast<const u32x4*>(kt + Tile4::k_off(32 * (e >> 1) + ql, 2 * (e & 1) + hh));
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        st[e >> 1] = mfma_f4(f[e], qf[e & 1], (e & 1) ? st[e >> 1] : (start ? *start : f32x16{0}),
+                             spread_byte(sc[e >> 1], 2 * (e & 1) + hh), qs[e & 1]);
+}
+
+struct Mx4Params {
+    const uint8_t* Q;       // [B, Hq, N, 64] E2M1 pairs
+    const uint8_t* Qs;      // [B, Hq, N, 4] E8M0
+    const uint8_t* K;       // [B, Hkv, N, 64]
+    const uint8_t* Ks;      // [B, Hkv, N, 4]
+    const uint8_t* Vt;      // [B, Hkv, Tc, 128, 64] E4M3, as in the FP8 path
+    const uint8_t* Krepr;   // [B, Hkv, Tc, 128] E5M2
+    const uint8_t* KreprS;  // [B, Hkv, Tc, 4] E8M0
+    uint16_t* O;
+    float* LSE;
+    int B, Hq, Hkv, N, Tr, Tc;
+    int causal, n_sink, n_local, use_minit;
+    float c;          // softmax scale * log2(e) (1 when FOLD)
+    float descale_v;
+    float headroom;
+};
+
+// As attn_fp8_kernel with the score product on MXFP4 operands.  FOLD (Alg. 1 only, softmax scale * log2(e) = 1,
+// i.e. the caller folded that factor into Q before quantising): frozen tiles start their accumulators at
+// -(m + H) and go to exp2 untouched.
+template <int MODE, bool FOLD>
+__global__ __launch_bounds__(256, 3) void attn_mx4_kernel(const Mx4Params p) {
+    static_assert(!FOLD || MODE == MODE_VFA, "folding needs a max that is known before the tile");
+    constexpr int D = 128, BM = 128, DB = 4;
+    // Alg. 1 keeps exp(S - m) in E5M2: the summaries of MXFP4 keys collect the upward rounding errors of 64 keys per
+    // feature, so the seeded max can sit ten binades above the scores, more than E4M3 has to spare
+    constexpr bool P_BF8 = MODE == MODE_VFA;
+    // two K stages of 4 KiB (together: the 8 KiB summary tile of the m-initialisation), two V^T stages of 8 KiB
+    __shared__ __attribute__((aligned(16))) uint8_t smem[2 * Tile4::KBYTES + 2 * Tile8::VBYTES];
+    __shared__ uint32_t kscale[2][BN];
+    uint8_t* const Ksm = smem;
+    uint8_t* const Vsm = smem + 2 * Tile4::KBYTES;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ql = lane & 31, hh = lane >> 5;
+    const int g = p.Hq / p.Hkv;
+    int b, h, i;
+    {
+        const int id = blockIdx.x, G = p.B * p.Hkv;
+        if ((G & 7) == 0) {
+            const int x = id & 7, y = id >> 3;
+            const int per = p.Tr * g;
+            const int kvl = y / per, rem = y - kvl * per;
+            i = p.Tr - 1 - rem / g;
+            const int kv = kvl * 8 + x;
+            b = kv / p.Hkv;
+            h = (kv - b * p.Hkv) * g + rem % g;
+        } else {
+            const int bh = id % (p.B * p.Hq);
+            i = p.Tr - 1 - id / (p.B * p.Hq);
+            b = bh / p.Hq;
+            h = bh - b * p.Hq;
+        }
+    }
+    const int hkv = h / g, N = p.N;
+    const int row0 = i * BM, last_row = min(N, row0 + BM) - 1;
+    const int a_lo = row0 / BN, a_hi = last_row / BN;
+    const int j_hi = p.causal ? a_hi : p.Tc - 1;
+    const uint8_t* Kg = p.K + ((size_t)(b * p.Hkv + hkv) * N) * 64;
+    const uint8_t* Ksg = p.Ks + ((size_t)(b * p.Hkv + hkv) * N) * 4;
+    const uint8_t* Vg = p.Vt + ((size_t)(b * p.Hkv + hkv) * p.Tc) * Tile8::VBYTES;
+    const int qrow = row0 + 32 * wave + ql, qrow_c = min(qrow, N - 1);
+    const int limit = p.causal ? qrow_c : N - 1;
+    u32x4 qf[2];
+    int qs[2];
+    {
+        const size_t qr = (size_t)(b * p.Hq + h) * N + qrow_c;
+        const uint32_t sw = *reinterpret_cast<const uint32_t*>(p.Qs + qr * 4);
+#pragma unroll
+        for (int kh = 0; kh < 2; ++kh) {
+            qf[kh] = *reinterpret_cast<const u32x4*>(p.Q + qr * 64 + 32 * kh + 16 * hh);
+            qs[kh] = spread_byte(sw, 2 * kh + hh);
+        }
+    }
+    auto load_k = [&](int j, int buf) __attribute__((always_inline)) {
+        load_tile4(Kg, j * BN, N, Ksm + buf * Tile4::KBYTES, wave, lane);
+        if (wave == 0) load_scales64(Ksg, j * BN, N, kscale[buf], lane);
+    };
+    float m2 = -INFINITY;
+    if (MODE == MODE_VFA && p.use_minit) {
+        const uint8_t* Rg = p.Krepr + ((size_t)(b * p.Hkv + hkv) * p.Tc) * D;
+        const uint8_t* RSg = p.KreprS + ((size_t)(b * p.Hkv + hkv) * p.Tc) * 4;
+        float mx = -INFINITY;
+        for (int ts = 0; ts * BN <= j_hi; ++ts) {
+            __syncthreads();
+            load_tile8<false, 4>(Rg, ts * BN, p.Tc, Ksm, wave, lane);
+            if (wave == 0) load_scales64(RSg, ts * BN, p.Tc, kscale[0], lane);
+            wait_vm0_and_sync();
+            f32x16 st[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int row = 32 * t + ql;
+                const uint32_t sc = kscale[0][row];
+#pragma unroll
+                for (int kh = 0; kh < 2; ++kh) {
+                    // 8-bit operand: bytes 0..15 of half hh are k = 16 hh + j, bytes 16..31 are k = 32 + 16 hh + j
+                    const int c0 = 4 * kh + hh;
+                    const i32x8 f = lds_frag8(Ksm + Tile8::k_off(row, c0), Ksm + Tile8::k_off(row, c0 + 2));
+                    st[t] = mfma_bf8_f4(f, qf[kh], kh ? st[t] : f32x16{0}, spread_byte(sc, 2 * kh + hh), qs[kh]);
+                }
+            }
+            mx = fmaxf(mx, tile_rowmax<true>(st, ts * BN, j_hi, hh));
+        }
+        m2 = xhalf_max(mx) * p.c;
+        __syncthreads();
+    }
+    Params vp{};
+    vp.n_sink = p.n_sink; vp.n_local = p.n_local;
+    const Visit vis = make_visit<MODE>(vp, a_lo, a_hi, j_hi);
+    f32x16 ot[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) ot[db] = f32x16{0};
+    float lsum = 0.f;
+    {
+        const int j0 = vis.tile(0);
+        load_k(j0, 0);
+        load_tile8<true, 4>(Vg + (size_t)j0 * Tile8::VBYTES, 0, 0, Vsm, wave, lane);
+        wait_vm0_and_sync();
+    }
+    f32x16 start;  // FOLD: -(m + H) of this lane's query in all 16 registers, set once the max is frozen
+    auto visit = [&](int k, auto special_c, auto masked_c) __attribute__((always_inline)) {
+        constexpr bool SPECIAL = decltype(special_c)::value, MASKED = decltype(masked_c)::value;
+        const int j = vis.tile(k), buf = k & 1;
+        if (k + 1 < vis.total) {
+            const int jn = vis.tile(k + 1);
+            load_k(jn, buf ^ 1);
+            load_tile8<true, 4>(Vg + (size_t)jn * Tile8::VBYTES, 0, 0, Vsm + (buf ^ 1) * Tile8::VBYTES, wave, lane);
+        }
+        f32x16 st[2];
+        uint32_t pk[8];
+        __builtin_amdgcn_s_setprio(1);
+        if (FOLD && !SPECIAL) qk_tile4(Ksm + buf * Tile4::KBYTES, kscale[buf], qf, qs, st, ql, hh, &start);
+        else qk_tile4(Ksm + buf * Tile4::KBYTES, kscale[buf], qf, qs, st, ql, hh);
+        __builtin_amdgcn_s_setprio(0);
+        const bool needs_mask = (p.causal && j * BN + BN - 1 > row0) || (j + 1) * BN > N;
+        if (FOLD && !SPECIAL) softmax_tile8_folded<MASKED, P_BF8>(st, pk, lsum, j * BN, needs_mask ? limit : 0x3fffffff, hh);
+        else softmax_tile8<SPECIAL, MASKED, P_BF8>(st, pk, ot, m2, lsum, p.c, p.headroom, j * BN, needs_mask ? limit : 0x3fffffff, hh);
+        __builtin_amdgcn_s_setprio(1);
+        pv_tile8<P_BF8>(Vsm + buf * Tile8::VBYTES, pk, ot, lane, hh);
+        __builtin_amdgcn_s_setprio(0);
+        wait_vm0_and_sync();
+    };
+    using std::false_type;
+    using std::true_type;
+    constexpr bool TAIL_SPECIAL = is_fa(MODE);
+    const int n_lead = TAIL_SPECIAL ? 0 : min(vis.n_special, vis.total);
+    int k_fast_end;
+    {
+        int j_masked = p.causal ? a_lo : p.Tc;
+        if (N % BN) j_masked = min(j_masked, p.Tc - 1);
+        int cnt = max(0, j_masked - vis.n1);
+        if (vis.n2 > 0) cnt -= max(0, min(j_masked, vis.s2 + vis.n2) - vis.s2);
+        k_fast_end = max(n_lead, min(vis.total, n_lead + cnt));
+    }
+    int k = 0;
+    for (; k < n_lead; ++k) visit(k, true_type{}, true_type{});
+    if (FOLD) {
+        const float v = -(m2 + p.headroom);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) start[r] = v;
+    }
+    for (; k < k_fast_end; ++k) visit(k, std::integral_constant<bool, TAIL_SPECIAL>{}, false_type{});
+    for (; k < vis.total; ++k) visit(k, std::integral_constant<bool, TAIL_SPECIAL>{}, true_type{});
+    const float l = xhalf_sum(lsum);
+    const float inv = l > 0.f ? p.descale_v * (P_BF8 ? 0x1p-15f : 0x1p-8f) / l : 0.f;
+    if (qrow < N) {
+        uint16_t* Og = p.O + ((size_t)(b * p.Hq + h) * N + qrow) * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const u32x2 w = {pack_bf16(ot[db][4 * q4] * inv, ot[db][4 * q4 + 1] * inv),
+                                 pack_bf16(ot[db][4 * q4 + 2] * inv, ot[db][4 * q4 + 3] * inv)};
+                *reinterpret_cast<u32x2*>(Og + 32 * db + 8 * q4 + 4 * hh) = w;
+            }
+        if (p.LSE && hh == 0)
+            p.LSE[(size_t)(b * p.Hq + h) * N + qrow] =
+                l > 0.f ? (m2 + p.headroom + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -2215,6 +2565,77 @@ int vfa_fp8_attn_fwd(int frozen, const void* Q8, const void* K8, const void* Vt8
     if (fold) attn_fp8_kernel<MODE_VFA, true><<<grid, 256, 0, s>>>(p);
     else if (frozen) attn_fp8_kernel<MODE_VFA, false><<<grid, 256, 0, s>>>(p);
     else attn_fp8_kernel<MODE_FA, false><<<grid, 256, 0, s>>>(p);
+    return hipGetLastError() == hipSuccess ? VFA_OK : VFA_ERR_HIP;
+}
+
+size_t vfa_mxfp4_workspace_bytes(int B, int Hkv, int N) {
+    if (B <= 0 || Hkv <= 0 || N <= 0) return 0;
+    const size_t bytes = (size_t)B * Hkv * ceil_div(N, BN) * (128 + 4);
+    return (bytes + 255) & ~(size_t)255;
+}
+
+int vfa_mxfp4_quantize(const void* X, void* X4, void* XS, long long n, float pre_scale, void* stream) {
+    if (n < 0 || (n & 31) || !(pre_scale > 0.f) || !isfinite(pre_scale)) return VFA_ERR_INVALID_ARG;
+    if (n == 0) return VFA_OK;
+    if (!X || !X4 || !XS || !aligned16(X) || (reinterpret_cast<uintptr_t>(X4) & 3u)) return VFA_ERR_INVALID_ARG;
+    const long long n8 = n / 8, blocks = (n8 + 255) / 256;
+    if (blocks > 0x7fffffffLL) return VFA_ERR_UNSUPPORTED;
+    (void)hipGetLastError();
+    mx4_quantize_kernel<<<(unsigned)blocks, 256, 0, (hipStream_t)stream>>>((const uint16_t*)X, (uint8_t*)X4, (uint8_t*)XS, n8,
+                                                                          pre_scale);
+    return hipGetLastError() == hipSuccess ? VFA_OK : VFA_ERR_HIP;
+}
+
+int vfa_mxfp4_attn_fwd(int frozen, const void* Q4, const void* QS, const void* K4, const void* KS, const void* Vt8, void* O,
+                       float* LSE, int B, int Hq, int Hkv, int N, int d, int block_m, int block_n, int causal, int n_sink,
+                       int n_local, int use_minit, float softmax_scale, float descale_v, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+    if (B < 0 || N < 0 || Hq <= 0 || Hkv <= 0 || d <= 0 || block_m <= 0 || block_n <= 0) return VFA_ERR_INVALID_ARG;
+    if (Hq % Hkv != 0 || (frozen != 0 && frozen != 1)) return VFA_ERR_INVALID_ARG;
+    if (!(descale_v > 0.f) || !isfinite(descale_v) || !isfinite(softmax_scale)) return VFA_ERR_INVALID_ARG;
+    if (frozen) {
+        if (n_sink < 0 || n_local < 0 || use_minit < 0 || use_minit > 2) return VFA_ERR_INVALID_ARG;
+        if (!use_minit && n_sink + n_local == 0) return VFA_ERR_INVALID_ARG;
+    }
+    if (d != 128 || block_m != 128 || block_n != BN) return VFA_ERR_UNSUPPORTED;
+    if (B == 0 || N == 0) return VFA_OK;
+    if (!Q4 || !QS || !K4 || !KS || !Vt8 || !O) return VFA_ERR_INVALID_ARG;
+    if (!aligned16(Q4) || !aligned16(K4) || !aligned16(Vt8) || !aligned16(O)) return VFA_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(QS) & 3u) || (reinterpret_cast<uintptr_t>(KS) & 3u)) return VFA_ERR_INVALID_ARG;
+    if (LSE && (reinterpret_cast<uintptr_t>(LSE) & 3u)) return VFA_ERR_INVALID_ARG;
+    const int Tc = ceil_div(N, BN), Tr = ceil_div(N, block_m);
+    if ((long long)B * Hq * Tr > 0x7fffffffLL || (long long)B * Hq * N > 0x7fffffffLL || (long long)B * Hkv > 65535)
+        return VFA_ERR_UNSUPPORTED;
+    const bool minit = frozen && use_minit;
+    if (minit && (!workspace || !aligned16(workspace) || workspace_bytes < vfa_mxfp4_workspace_bytes(B, Hkv, N)))
+        return VFA_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    uint8_t* const repr = (uint8_t*)workspace;
+    uint8_t* const repr_s = repr ? repr + (size_t)B * Hkv * Tc * 128 : nullptr;  // (a multiple of 128: dword aligned)
+    (void)hipGetLastError();
+    if (minit && use_minit == 1) {
+        mx4_kblock_summary_kernel<<<dim3((unsigned)Tc, (unsigned)(B * Hkv)), 128, 0, s>>>((const uint8_t*)K4, (const uint8_t*)KS,
+                                                                                         repr, repr_s, N, Tc);
+        if (hipGetLastError() != hipSuccess) return VFA_ERR_HIP;
+    }
+    Mx4Params p{};
+    p.Q = (const uint8_t*)Q4; p.Qs = (const uint8_t*)QS; p.K = (const uint8_t*)K4; p.Ks = (const uint8_t*)KS;
+    p.Vt = (const uint8_t*)Vt8; p.Krepr = repr; p.KreprS = repr_s;
+    p.O = (uint16_t*)O; p.LSE = LSE;
+    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N; p.Tr = Tr; p.Tc = Tc;
+    p.causal = causal ? 1 : 0; p.n_sink = n_sink; p.n_local = n_local; p.use_minit = minit ? 1 : 0;
+    const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)d);
+    p.c = scale * kLog2e;
+    p.descale_v = descale_v;
+    p.headroom = frozen ? 4.f : 0.f;
+    // Alg. 1 with the scores already in log2 units (the caller multiplied Q by scale * log2(e) before quantising
+    // and passes softmax_scale = ln 2): nothing is left to multiply, and the frozen max becomes the accumulators' start
+    const bool fold = frozen && fabsf(p.c - 1.f) <= 0x1p-18f;
+    if (fold) p.c = 1.f;
+    const dim3 grid((unsigned)(B * Hq * Tr));
+    if (fold) attn_mx4_kernel<MODE_VFA, true><<<grid, 256, 0, s>>>(p);
+    else if (frozen) attn_mx4_kernel<MODE_VFA, false><<<grid, 256, 0, s>>>(p);
+    else attn_mx4_kernel<MODE_FA, false><<<grid, 256, 0, s>>>(p);
     return hipGetLastError() == hipSuccess ? VFA_OK : VFA_ERR_HIP;
 }
 

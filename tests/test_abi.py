@@ -120,6 +120,22 @@ def test_bad_arguments_are_rejected_before_launch(pkg):
     assert f8(0, p, p, p, p, none, 1, 4, 2, 256, 64, 128, 64, 1, 1, 1, 1, 0.0, 1.0, 1.0, 1.0, p, 1 << 20, none) == -2   # d = 64
     assert f8(0, none, p, p, p, none, *f8shape, 1, 1, 1, 0.0, 1.0, 1.0, 1.0, p, 1 << 20, none) == -1
     assert f8(0, p, p, p, p, none, 0, 4, 2, 256, 128, 128, 64, 1, 1, 1, 1, 0.0, 1.0, 1.0, 1.0, none, 0, none) == 0
+    m4 = lambda *a: L.vfa_mxfp4_attn_fwd(*a)
+    # frozen, Q4, QS, K4, KS, Vt8, O, LSE, shape, n_sink, n_local, use_minit, softmax_scale, descale_v, workspace, bytes, stream
+    assert m4(1, p, p, p, p, p, p, none, *f8shape, 1, 1, 1, 0.0, 1.0, none, 0, none) == -1             # summaries need a workspace
+    assert m4(1, p, p, p, p, p, p, none, *f8shape, 1, 1, 1, 0.0, 1.0, p, 256, none) == -1              # ... of 4 * 132 * 2 bytes
+    assert m4(1, p, p, p, p, p, p, none, *f8shape, 1, 1, 1, 0.0, 0.0, p, 1 << 20, none) == -1          # descale_v must be > 0
+    assert m4(2, p, p, p, p, p, p, none, *f8shape, 1, 1, 1, 0.0, 1.0, p, 1 << 20, none) == -1          # frozen is 0 or 1
+    assert m4(1, p, p, p, p, p, p, none, *f8shape, 0, 0, 0, 0.0, 1.0, p, 1 << 20, none) == -1          # max would stay -inf
+    assert m4(0, p, none, p, p, p, p, none, *f8shape, 1, 1, 1, 0.0, 1.0, p, 1 << 20, none) == -1       # scales missing
+    assert m4(0, p, ctypes.c_void_p(0x1002), p, p, p, p, none, *f8shape, 1, 1, 1, 0.0, 1.0, p, 1 << 20, none) == -1
+    assert m4(0, p, p, p, p, p, p, none, 1, 4, 2, 256, 64, 128, 64, 1, 1, 1, 1, 0.0, 1.0, p, 1 << 20, none) == -2   # d = 64
+    assert m4(0, p, p, p, p, p, p, none, 0, 4, 2, 256, 128, 128, 64, 1, 1, 1, 1, 0.0, 1.0, none, 0, none) == 0
+    assert L.vfa_mxfp4_quantize(p, p, p, 48, 1.0, none) == -1                                         # not a multiple of 32
+    assert L.vfa_mxfp4_quantize(p, p, p, 64, 0.0, none) == -1
+    assert L.vfa_mxfp4_quantize(p, none, p, 64, 1.0, none) == -1
+    assert L.vfa_mxfp4_quantize(p, p, p, 0, 1.0, none) == 0
+    assert L.vfa_mxfp4_workspace_bytes(1, 2, 256) == 1280 and L.vfa_mxfp4_workspace_bytes(0, 2, 256) == 0
     assert L.vfa_fp8_quantize(p, p, 12, 1.0, none) == -1                                              # not a multiple of 8
     assert L.vfa_fp8_quantize(p, p, 16, -1.0, none) == -1
     assert L.vfa_fp8_quantize(p, p, 0, 1.0, none) == 0

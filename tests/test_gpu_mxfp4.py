@@ -1,0 +1,216 @@
+"""GPU parity of the MXFP4 score path.  The pre-passes (MX quantiser, key-block summaries) are byte-exact
+against the oracle's codec; the attention call is compared with the float64 oracle run on the DEQUANTISED
+operands, so what is left is the rounding of exp(S - m) to 8 bits plus the bf16 output, as for the FP8 path:
+E4M3 under the exact max (relative error <= 2^-4 per entry, which bounds |O_gpu - O| by 2^-4 * max|V| row by row),
+E5M2 under the frozen max (2^-3: one mantissa bit traded for range, because the summaries of MXFP4 keys overshoot)."""
+import math
+
+import numpy as np
+import pytest
+
+from paper_2604_12798_amd import workloads as wl
+
+from gpu_util import LSE_ABS, gather_blocks, gpu_inputs, host_f32
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def vfa():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2604_12798_amd as pkg
+    pkg.lib()
+    return pkg
+
+
+def W(base="cfg2", **kw):
+    return wl.small(wl.CONFIGS[base], **kw)
+
+
+def pow2_scale(x):
+    return 2.0 ** math.ceil(math.log2(float(np.abs(x).max()) / 448.0))
+
+
+def aligned_queries_and_keys(w, seed=5):
+    """Inside each 64-key block the keys are one random vector with 5 % jitter, and every query is the vector of one
+    block it can see plus 30 % noise (bf16 bit patterns).  The summary of a block is then close to each of its keys,
+    so the seeds are tight also after the 4-bit rounding, and a row's largest score (about sqrt(d) nats) towers over
+    the rest: a seed computed from wrongly paired features would sit far below it and the exponentials would cap."""
+    rng = np.random.default_rng(seed)
+    base = rng.standard_normal((w.B, w.Hkv, w.Tc, 1, w.d))
+    K = (base * (1 + 0.05 * rng.standard_normal((w.B, w.Hkv, w.Tc, w.block_n, w.d)))).reshape(w.B, w.Hkv, -1, w.d)[:, :, :w.N]
+    rows = np.arange(w.N)
+    Q = np.empty((w.B, w.Hq, w.N, w.d))
+    for b in range(w.B):
+        for h in range(w.Hq):
+            target = rng.integers(0, rows // w.block_n + 1)             # a block at or before the row's own
+            Q[b, h] = base[b, h // (w.Hq // w.Hkv), target, 0] + 0.3 * rng.standard_normal((w.N, w.d))
+    bits = lambda x: wl.f32_to_bf16_bits(np.ascontiguousarray(x, dtype=np.float32))
+    return bits(Q), bits(K)
+
+
+def mx_problem(vfa, oracle, w, fold, seed=wl.DEFAULT_SEED, qk=None):
+    """Q, K -> MXFP4 (GPU pre-pass for the library, oracle codec for the reference), V -> E4M3 tiles.
+    fold: Q is multiplied by scale * log2(e) before quantising, and the attention runs with softmax_scale = ln 2."""
+    import torch
+    t = wl.generate(w, seed)
+    if qk is not None:
+        t["Q"], t["K"] = qk
+    Q, K, V = gpu_inputs(t)
+    Qh, Kh, Vh = host_f32(t)
+    pre = float(np.float32(1.0 / math.sqrt(w.d)) * np.float32(math.log2(math.e))) if fold else 1.0
+    Q4, QS = vfa.mxfp4_quantize(Q, pre)
+    K4, KS = vfa.mxfp4_quantize(K)
+    sv = pow2_scale(Vh)
+    Vt8 = vfa.fp8_pack_v(V, 1 / sv)
+    torch.cuda.synchronize()
+    cq, sq = oracle.mx_quantize(Qh, 0, pre)
+    ck, sk = oracle.mx_quantize(Kh, 0)
+    cv = oracle.e4m3_quantize(Vh, 1 / sv)
+    return dict(Q4=Q4, QS=QS, K4=K4, KS=KS, Vt8=Vt8, sv=sv, cq=cq, sq=sq, ck=ck, sk=sk,
+                Qd=oracle.mx_dequantize(cq, sq).astype(np.float32), Kd=oracle.mx_dequantize(ck, sk).astype(np.float32),
+                Vd=oracle.e4m3_dequantize(cv, sv).astype(np.float32),
+                scale=math.log(2.0) if fold else 1.0 / math.sqrt(w.d))
+
+
+SHAPES = [
+    ("gqa_causal_1024", W(B=2, Hq=4, Hkv=2, N=1024)),
+    ("mha_noncausal_768", W(B=1, Hq=2, Hkv=2, N=768, causal=False)),
+    ("ragged_1000", W(B=1, Hq=2, Hkv=1, N=1000)),
+    ("sink2_local2", W(B=1, Hq=2, Hkv=2, N=1280, n_sink=2, n_local=2)),
+]
+
+
+@pytest.mark.parametrize("name,w", SHAPES[:3], ids=[s[0] for s in SHAPES[:3]])
+@pytest.mark.parametrize("fold", [False, True], ids=["plain", "prescaled"])
+def test_quantiser_is_byte_exact(vfa, oracle, name, w, fold):
+    pr = mx_problem(vfa, oracle, w, fold)
+    for what, got, want in (("Q codes", pr["Q4"], pr["cq"]), ("Q scales", pr["QS"], pr["sq"]),
+                            ("K codes", pr["K4"], pr["ck"]), ("K scales", pr["KS"], pr["sk"])):
+        assert np.array_equal(got.cpu().numpy(), want), what
+    # the dequantised values are on the E2M1 grid of their block and within a quarter of the block maximum of the input
+    t = wl.generate(w)
+    Kh = host_f32(t)[1].astype(np.float64)
+    blk = lambda a: a.reshape(a.shape[:-1] + (4, 32))
+    amax = np.abs(blk(Kh)).max(-1, keepdims=True)
+    assert np.all(np.abs(blk(pr["Kd"].astype(np.float64)) - blk(Kh)) <= amax / 4 * (1 + 1e-12))
+
+
+@pytest.mark.parametrize("name,w", SHAPES[:3], ids=[s[0] for s in SHAPES[:3]])
+def test_summaries_are_byte_exact(vfa, oracle, name, w):
+    """Summary of a key block = sabsmax of the dequantised keys, held as MX blocks of E5M2 elements."""
+    import torch
+    pr = mx_problem(vfa, oracle, w, False)
+    _, _, ws = vfa.mxfp4_attn_fwd(pr["Q4"], pr["QS"], pr["K4"], pr["KS"], pr["Vt8"], descale_v=pr["sv"], frozen=True,
+                                  causal=w.causal, n_sink=w.n_sink, n_local=w.n_local)
+    torch.cuda.synchronize()
+    n = w.B * w.Hkv * w.Tc
+    raw = ws.cpu().numpy()
+    got_c, got_s = raw[:n * 128].reshape(w.B, w.Hkv, w.Tc, 128), raw[n * 128:n * 132].reshape(w.B, w.Hkv, w.Tc, 4)
+    R = oracle.sabsmax(pr["Kd"], w.block_n)
+    assert np.array_equal(R.astype(np.float32).astype(np.float64), R)
+    want_c, want_s = oracle.mx_quantize(R.astype(np.float32), 1)
+    zero = lambda c: np.where(c == 0x80, 0, c)       # a column of zeros may carry either sign
+    assert np.array_equal(got_s, want_s)
+    assert np.array_equal(zero(got_c), zero(want_c))
+    # and the E5M2 blocks lose nothing of the summaries on this data
+    assert np.array_equal(oracle.mx_dequantize(want_c, want_s, 1), R)
+
+
+@pytest.mark.parametrize("name,w", SHAPES, ids=[s[0] for s in SHAPES])
+@pytest.mark.parametrize("fold", [False, True], ids=["plain", "prescaled"])
+def test_mxfp4_attention_matches_oracle_on_dequantised_operands(vfa, oracle, name, w, fold):
+    import torch
+    pr = mx_problem(vfa, oracle, w, fold)
+    blocks = wl.all_blocks(w)
+    Oe, Le, Me = oracle.exact(pr["Qd"], pr["Kd"], pr["Vd"], w.block_m, w.causal, blocks, scale=pr["scale"])
+    vmax = float(np.abs(pr["Vd"]).max())
+    kw = dict(descale_v=pr["sv"], block_m=w.block_m, block_n=w.block_n, causal=w.causal,
+              softmax_scale=pr["scale"] if fold else 0.0)
+    valid = ~np.isnan(Le)
+    for frozen in (False, True):
+        O, L, _ = vfa.mxfp4_attn_fwd(pr["Q4"], pr["QS"], pr["K4"], pr["KS"], pr["Vt8"], frozen=frozen, n_sink=w.n_sink,
+                                     n_local=w.n_local, **kw)
+        torch.cuda.synchronize()
+        got_O, got_L = gather_blocks(O, blocks, w.block_m, w.N), gather_blocks(L, blocks, w.block_m, w.N)
+        assert not np.isnan(got_O[valid]).any()
+        err = np.abs(got_O[valid] - Oe[valid])
+        lerr = np.abs(got_L[valid] - Le[valid]).max()
+        print(name, "prescaled" if fold else "plain", "frozen" if frozen else "online",
+              "max_abs %.4f mean_abs %.5f lse %.2e (bound %.3f)" % (err.max(), err.mean(), lerr, vmax / 16), flush=True)
+        bound = vmax / (8 if frozen else 16)
+        assert err.max() <= bound * 1.05 + 2e-2
+        assert err.mean() <= bound / 8
+        assert lerr <= LSE_ABS
+    ref = oracle.blocks(pr["Qd"], pr["Kd"], pr["Vd"], w.block_m, w.block_n, w.causal, blocks, n_sink=w.n_sink,
+                        n_local=w.n_local, scale=pr["scale"])
+    gap = (Me - ref["m_final"])[~np.isnan(Me)]
+    print(name, "true max minus frozen max (nats): min %.2f max %.2f (headroom 2.77)" % (gap.min(), gap.max()), flush=True)
+    assert gap.max() < 2.77
+
+
+@pytest.mark.parametrize("name,w", SHAPES[:2], ids=[s[0] for s in SHAPES[:2]])
+@pytest.mark.parametrize("fold", [False, True], ids=["plain", "prescaled"])
+def test_mxfp4_seed_alone_carries_the_softmax(vfa, oracle, name, w, fold):
+    """No sink and no local blocks: the max never moves off the seed, so the result is right only if the
+    m-initialisation (E5M2 summaries times E2M1 queries in one instruction) produced the oracle's seeds."""
+    import torch
+    pr = mx_problem(vfa, oracle, w, fold, qk=aligned_queries_and_keys(w))
+    blocks = wl.all_blocks(w)
+    Oe, Le, Me = oracle.exact(pr["Qd"], pr["Kd"], pr["Vd"], w.block_m, w.causal, blocks, scale=pr["scale"])
+    ref = oracle.blocks(pr["Qd"], pr["Kd"], pr["Vd"], w.block_m, w.block_n, w.causal, blocks, n_sink=0, n_local=0,
+                        scale=pr["scale"])
+    gap = (Me - ref["m_final"])[~np.isnan(Me)]
+    print(name, "seed-only gap (nats): min %.2f max %.2f" % (gap.min(), gap.max()), flush=True)
+    assert gap.max() < 2.77, "the oracle's own seeds leave the headroom on this input: choose another"
+    O, L, _ = vfa.mxfp4_attn_fwd(pr["Q4"], pr["QS"], pr["K4"], pr["KS"], pr["Vt8"], frozen=True, n_sink=0, n_local=0,
+                                 descale_v=pr["sv"], causal=w.causal, softmax_scale=pr["scale"] if fold else 0.0)
+    torch.cuda.synchronize()
+    got_O, got_L = gather_blocks(O, blocks, w.block_m, w.N), gather_blocks(L, blocks, w.block_m, w.N)
+    valid = ~np.isnan(Le)
+    vmax = float(np.abs(pr["Vd"]).max())
+    err = np.abs(got_O[valid] - Oe[valid])
+    lerr = np.abs(got_L[valid] - Le[valid]).max()
+    print(name, "seed-only max_abs %.4f mean_abs %.5f lse %.2e" % (err.max(), err.mean(), lerr), flush=True)
+    assert err.max() <= vmax / 8 * 1.05 + 2e-2 and err.mean() <= vmax / 8 / 8 and lerr <= LSE_ABS
+
+
+def test_mxfp4_frozen_max_far_too_low_is_capped_not_nan(vfa, oracle):
+    """No m-init and a single local block: rows whose maximum lies in a far (frozen) tile exceed the 4-binade
+    headroom; the result is then not exact, but it must stay finite and normalised (|O| <= max|V|)."""
+    import torch
+    w = W("cfg4", B=1, Hq=2, Hkv=2, N=2048)
+    pr = mx_problem(vfa, oracle, w, False)
+    O, L, _ = vfa.mxfp4_attn_fwd(pr["Q4"], pr["QS"], pr["K4"], pr["KS"], pr["Vt8"], frozen=True, use_minit=False, n_sink=1,
+                                 n_local=1, descale_v=pr["sv"], causal=False)
+    torch.cuda.synchronize()
+    o = O.float().cpu().numpy()
+    assert np.isfinite(o).all() and np.isfinite(L.cpu().numpy()).all()
+    assert np.abs(o).max() <= float(np.abs(pr["Vd"]).max()) * 1.01
+
+
+def test_mxfp4_full_size_sampled_blocks(vfa, oracle):
+    """cfg3 in the launch configurations bench.py times (online, Alg. 1, Alg. 1 on prescaled queries), checked on a
+    sample of query blocks."""
+    import torch
+    w = wl.CONFIGS["cfg3"]
+    blocks = wl.sample_blocks(w, 6)
+    for fold in (False, True):
+        pr = mx_problem(vfa, oracle, w, fold)
+        Oe, Le, Me = oracle.exact(pr["Qd"], pr["Kd"], pr["Vd"], w.block_m, w.causal, blocks, scale=pr["scale"])
+        vmax = float(np.abs(pr["Vd"]).max())
+        for frozen in ((False, True) if not fold else (True,)):
+            O, L, _ = vfa.mxfp4_attn_fwd(pr["Q4"], pr["QS"], pr["K4"], pr["KS"], pr["Vt8"], frozen=frozen, n_sink=w.n_sink,
+                                         n_local=w.n_local, descale_v=pr["sv"], block_m=w.block_m, block_n=w.block_n,
+                                         causal=w.causal, softmax_scale=pr["scale"] if fold else 0.0)
+            torch.cuda.synchronize()
+            got_O, got_L = gather_blocks(O, blocks, w.block_m, w.N), gather_blocks(L, blocks, w.block_m, w.N)
+            err = np.abs(got_O - Oe)
+            lerr = np.abs(got_L - Le).max()
+            print("cfg3 mxfp4", "prescaled" if fold else "plain", "frozen" if frozen else "online",
+                  "max_abs %.4f mean_abs %.5f lse %.2e" % (err.max(), err.mean(), lerr), flush=True)
+            bound = vmax / (8 if frozen else 16)
+            assert not np.isnan(got_O).any()
+            assert err.max() <= bound * 1.05 + 2e-2 and err.mean() <= bound / 8 and lerr <= LSE_ABS
+        del pr
