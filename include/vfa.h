@@ -252,8 +252,11 @@ size_t vfa_mxfp4_workspace_bytes(int B, int Hkv, int N);
  * its descale_v.  Scores are (dequantised Q) . (dequantised K) * softmax_scale.  frozen = 0: online softmax
  * on every block; frozen = 1: Alg. 1, the summaries being the sabsmax of the dequantised keys held as MX
  * blocks of E5M2 elements (use_minit = 1 computes them into the workspace: [B, Hkv, Tc, 128] codes followed
- * by [B, Hkv, Tc, 4] scale bytes; 2 = the workspace already holds them).  exp(S - m), l, O and LSE as in
- * vfa_fp8_attn_fwd.  With frozen = 1 and softmax_scale * log2(e) = 1 (to 2^-18: the caller multiplied Q by
+ * by [B, Hkv, Tc, 4] scale bytes; 2 = the workspace already holds them).  l, O and LSE as in
+ * vfa_fp8_attn_fwd; exp(S - m) is rounded to E4M3 scaled by 2^8 for frozen = 0 and to E5M2 scaled by 2^15 for
+ * frozen = 1 (one mantissa bit less, 14 binades more: summaries of 4-bit keys collect the upward rounding
+ * errors of a whole block, so the seeded max can sit many binades above the scores; the 4 binades of headroom
+ * for scores ABOVE the frozen max are the same).  With frozen = 1 and softmax_scale * log2(e) = 1 (to 2^-18: the caller multiplied Q by
  * its scale * log2(e) before quantising and passes softmax_scale = ln 2) the frozen max enters as the start
  * value of the matrix instruction's accumulators and no per-score arithmetic but exp is left.
  * Errors as vfa_fp8_attn_fwd. */
