@@ -62,6 +62,8 @@ SHAPES = [
     ("mha_noncausal_768", W(B=1, Hq=2, Hkv=2, N=768, causal=False)),
     ("ragged_1000", W(B=1, Hq=2, Hkv=1, N=1000)),
     ("sink2_local2", W(B=1, Hq=2, Hkv=2, N=1280, n_sink=2, n_local=2)),
+    ("two_tiles_65", W(B=1, Hq=2, Hkv=1, N=65)),
+    ("one_key", W(B=2, Hq=2, Hkv=2, N=1)),
 ]
 
 
