@@ -399,19 +399,39 @@ __global__ __launch_bounds__(256) void fp8_pack_v_kernel(const uint16_t* __restr
     }
 }
 
-// sabsmax over E4M3 codes (sign-magnitude: the 7 low bits order the magnitudes; tie -> the positive code)
-__global__ __launch_bounds__(128) void fp8_kblock_summary_kernel(const uint8_t* __restrict__ K, uint8_t* __restrict__ R, int N,
+// sabsmax over E4M3 codes (sign-magnitude: the 7 low bits order the magnitudes; tie -> the positive code, the
+// smaller one; the rule is commutative and associative, so any reduction order gives the same bytes).
+// 256 threads: thread (rg, ch) takes the 16-byte chunk ch of rows rg and rg + 32 (rows past the end of a ragged
+// block repeat its last row, which changes nothing), then 128 threads fold the 32 partial rows of one feature each.
+__device__ __forceinline__ uint32_t fp8_sabs_pick(uint32_t a, uint32_t b) {
+    const uint32_t ma = a & 0x7f, mb = b & 0x7f;
+    return mb > ma ? b : (ma > mb ? a : min(a, b));
+}
+__global__ __launch_bounds__(256) void fp8_kblock_summary_kernel(const uint8_t* __restrict__ K, uint8_t* __restrict__ R, int N,
                                                                  int Tc) {
-    const int j = blockIdx.x, bh = blockIdx.y, t = threadIdx.x;
-    const uint8_t* base = K + ((size_t)bh * N + (size_t)j * BN) * 128 + t;
+    __shared__ u32x4 part[32][8];
+    const int j = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x;
+    const int rg = tid >> 3, ch = tid & 7;
     const int rows = min(BN, N - j * BN);
-    uint32_t best = base[0];
-    for (int r = 1; r < rows; ++r) {
-        const uint32_t x = base[(size_t)r * 128];
-        const uint32_t mb = best & 0x7f, mx = x & 0x7f;
-        best = mx > mb ? x : (mb > mx ? best : min(best, x));
+    const uint8_t* base = K + ((size_t)bh * N + (size_t)j * BN) * 128 + ch * 16;
+    const u32x4 a = *reinterpret_cast<const u32x4*>(base + (size_t)min(rg, rows - 1) * 128);
+    const u32x4 b = *reinterpret_cast<const u32x4*>(base + (size_t)min(rg + 32, rows - 1) * 128);
+    u32x4 best;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) w |= fp8_sabs_pick((a[e] >> (8 * q)) & 0xffu, (b[e] >> (8 * q)) & 0xffu) << (8 * q);
+        best[e] = w;
     }
-    R[((size_t)bh * Tc + j) * 128 + t] = (uint8_t)best;
+    part[rg][ch] = best;
+    __syncthreads();
+    if (tid < 128) {
+        const uint8_t* col = reinterpret_cast<const uint8_t*>(&part[0][0]) + tid;
+        uint32_t v = col[0];
+        for (int r = 1; r < 32; ++r) v = fp8_sabs_pick(v, col[r * 128]);
+        R[((size_t)bh * Tc + j) * 128 + tid] = (uint8_t)v;
+    }
 }
 
 }  // namespace

@@ -74,30 +74,42 @@ __global__ __launch_bounds__(256) void mx4_quantize_kernel(const uint16_t* __res
 
 // sabsmax of a block of MXFP4 keys, per feature over the dequantised values (tie -> the positive one), stored
 // as MX blocks of E5M2: scale byte = exponent field of the block maximum - 15; codes [B*Hkv, Tc, 128],
-// scales [B*Hkv, Tc, 4].  One thread per feature.
-__global__ __launch_bounds__(128) void mx4_kblock_summary_kernel(const uint8_t* __restrict__ K4, const uint8_t* __restrict__ KS,
+// scales [B*Hkv, Tc, 4].  256 threads: thread (row, blk) dequantises the 32 elements of MX block blk of key row
+// into LDS (rows past the end of a ragged block repeat its last row), then one thread per feature folds the 64
+// rows; the pick is commutative and associative up to the sign of a zero, which is set to + at the end.
+__global__ __launch_bounds__(256) void mx4_kblock_summary_kernel(const uint8_t* __restrict__ K4, const uint8_t* __restrict__ KS,
                                                                  uint8_t* __restrict__ R, uint8_t* __restrict__ RS, int N,
                                                                  int Tc) {
-    const int j = blockIdx.x, bh = blockIdx.y, t = threadIdx.x;
+    __shared__ float val[BN][128 + 1];
+    const int j = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x;
     const int rows = min(BN, N - j * BN);
-    const uint8_t* kc = K4 + ((size_t)bh * N + (size_t)j * BN) * 64 + (t >> 1);
-    const uint8_t* ks = KS + ((size_t)bh * N + (size_t)j * BN) * 4 + (t >> 5);
-    float best = 0.f;
-    for (int r = 0; r < rows; ++r) {
-        const uint32_t code = ((uint32_t)kc[(size_t)r * 64] >> (4 * (t & 1))) & 0xfu;
-        const float v = __builtin_ldexpf(e2m1_value(code), (int)ks[(size_t)r * 4] - 127);
-        const float av = fabsf(v), ab = fabsf(best);
-        best = (r == 0 || av > ab || (av == ab && v > best)) ? v : best;
-    }
-    best = best == 0.f ? 0.f : best;  // a column of zeros of either sign: +0
-    float amax = fabsf(best);
+    {
+        const int row = tid >> 2, blk = tid & 3;
+        const size_t r = (size_t)bh * N + (size_t)j * BN + min(row, rows - 1);
+        const u32x4 c = *reinterpret_cast<const u32x4*>(K4 + r * 64 + blk * 16);
+        const int e = (int)KS[r * 4 + blk] - 127;
 #pragma unroll
-    for (int o = 16; o >= 1; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));  // the 32 features of one MX block
-    const int ef = (int)((__float_as_uint(amax) >> 23) & 0xffu);
-    const int sb = max(ef - 15, 0);
-    const float y = __builtin_ldexpf(best, 127 - sb);  // at most 1.5 * 2^15: inside E5M2's finite range
-    R[((size_t)bh * Tc + j) * 128 + t] = (uint8_t)(__builtin_amdgcn_cvt_pk_bf8_f32(y, 0.f, 0, false) & 0xff);
-    if ((t & 31) == 0) RS[((size_t)bh * Tc + j) * 4 + (t >> 5)] = (uint8_t)sb;
+        for (int q = 0; q < 32; ++q) val[row][32 * blk + q] = __builtin_ldexpf(e2m1_value((c[q >> 3] >> (4 * (q & 7))) & 0xfu), e);
+    }
+    __syncthreads();
+    if (tid < 128) {
+        const int t = tid;
+        float best = val[0][t];
+        for (int r = 1; r < BN; ++r) {
+            const float v = val[r][t];
+            const float av = fabsf(v), ab = fabsf(best);
+            best = (av > ab || (av == ab && v > best)) ? v : best;
+        }
+        best = best == 0.f ? 0.f : best;  // a column of zeros of either sign: +0
+        float amax = fabsf(best);
+#pragma unroll
+        for (int o = 16; o >= 1; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));  // the 32 features of one MX block
+        const int ef = (int)((__float_as_uint(amax) >> 23) & 0xffu);
+        const int sb = max(ef - 15, 0);
+        const float y = __builtin_ldexpf(best, 127 - sb);  // at most 1.5 * 2^15: inside E5M2's finite range
+        R[((size_t)bh * Tc + j) * 128 + t] = (uint8_t)(__builtin_amdgcn_cvt_pk_bf8_f32(y, 0.f, 0, false) & 0xff);
+        if ((t & 31) == 0) RS[((size_t)bh * Tc + j) * 4 + (t >> 5)] = (uint8_t)sb;
+    }
 }
 
 __device__ __forceinline__ f32x16 mfma_f4(const u32x4& a, const u32x4& b, const f32x16& c, int scale_a, int scale_b) {

@@ -416,7 +416,7 @@ int vfa_fp8_attn_fwd(int frozen, const void* Q8, const void* K8, const void* Vt8
     hipStream_t s = (hipStream_t)stream;
     (void)hipGetLastError();
     if (minit && use_minit == 1) {
-        fp8_kblock_summary_kernel<<<dim3((unsigned)Tc, (unsigned)(B * Hkv)), 128, 0, s>>>((const uint8_t*)K8, (uint8_t*)workspace, N, Tc);
+        fp8_kblock_summary_kernel<<<dim3((unsigned)Tc, (unsigned)(B * Hkv)), 256, 0, s>>>((const uint8_t*)K8, (uint8_t*)workspace, N, Tc);
         if (hipGetLastError() != hipSuccess) return VFA_ERR_HIP;
     }
     Fp8Params p{};
@@ -494,7 +494,7 @@ int vfa_mxfp4_attn_fwd(int frozen, const void* Q4, const void* QS, const void* K
     uint8_t* const repr_s = repr ? repr + (size_t)B * Hkv * Tc * 128 : nullptr;  // (a multiple of 128: dword aligned)
     (void)hipGetLastError();
     if (minit && use_minit == 1) {
-        mx4_kblock_summary_kernel<<<dim3((unsigned)Tc, (unsigned)(B * Hkv)), 128, 0, s>>>((const uint8_t*)K4, (const uint8_t*)KS,
+        mx4_kblock_summary_kernel<<<dim3((unsigned)Tc, (unsigned)(B * Hkv)), 256, 0, s>>>((const uint8_t*)K4, (const uint8_t*)KS,
                                                                                          repr, repr_s, N, Tc);
         if (hipGetLastError() != hipSuccess) return VFA_ERR_HIP;
     }

@@ -83,6 +83,21 @@ def test_prepasses_are_byte_exact(vfa, oracle, name, w):
     assert np.array_equal(pr["Vt8"].cpu().numpy(), want)
 
 
+@pytest.mark.parametrize("name,w", SHAPES[:3] + SHAPES[4:], ids=[s[0] for s in SHAPES[:3] + SHAPES[4:]])
+def test_fp8_summaries_are_byte_exact(vfa, oracle, name, w):
+    """Summary of a key block = sabsmax of its dequantised keys = again an E4M3 code of that block (per-tensor scale)."""
+    import torch
+    pr = quantised_problem(vfa, oracle, w)
+    ws = torch.zeros(max(256, w.B * w.Hkv * w.Tc * 128), dtype=torch.uint8, device=pr["Q8"].device)
+    vfa.fp8_attn_fwd(pr["Q8"], pr["K8"], pr["Vt8"], frozen=True, descale_q=pr["sq"], descale_k=pr["sk"], descale_v=pr["sv"],
+                     causal=w.causal, n_sink=w.n_sink, n_local=w.n_local, workspace=ws)
+    torch.cuda.synchronize()
+    got = ws.cpu().numpy()[:w.B * w.Hkv * w.Tc * 128].reshape(w.B, w.Hkv, w.Tc, 128)
+    want = oracle.e4m3_quantize(oracle.sabsmax(pr["Kd"], w.block_n).astype(np.float32), 1 / pr["sk"])
+    zero = lambda c: np.where(c == 0x80, 0, c)       # a column of zeros may carry either sign
+    assert np.array_equal(zero(got), zero(want))
+
+
 @pytest.mark.parametrize("name,w", SHAPES, ids=[s[0] for s in SHAPES])
 def test_fp8_attention_matches_oracle_on_dequantised_operands(vfa, oracle, name, w):
     import torch
