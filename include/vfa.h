@@ -232,6 +232,24 @@ int vfa_fp8_attn_fwd(int frozen, const void* Q8, const void* K8, const void* Vt8
                      float descale_k, float descale_v, void* workspace, size_t workspace_bytes,
                      void* stream);
 
+/* Alg. 1 on E4M3 operands WITHOUT exponentials.  Needs what the fast path of vfa_fp8_attn_fwd needs (descale_q *
+ * descale_k * softmax_scale * log2(e) a power of two to 2^-18, else VFA_ERR_INVALID_ARG), because the scale and
+ * the frozen max must sit inside the matrix instruction.  The code of a small float read as an integer is a
+ * piecewise-linear logarithm of its value, so the E5M2 code of exp(S - m) is obtained from the score by a
+ * multiply-add (folded into the instruction) and one float-to-byte conversion: each weight is within
+ * [-11 %, +12 %] of the exact one (the format's own rounding would be +-12.5 %), and the row sum is taken over the
+ * SAME rounded weights by one more matrix instruction, so O is a properly normalised average of V under those
+ * weights (measured: mean-abs error as the rounded-exponential path, max-abs within 2^-3 max|V|).  LSE is computed
+ * from that row sum: within 0.12 nats of the exact value.  This is the performance discussion's argument taken to
+ * its end for 8-bit P: with the max known before the tile, no per-score vector arithmetic but a clamp and a
+ * conversion is left.  Everything else as vfa_fp8_attn_fwd with frozen = 1 (sink / local blocks keep the
+ * exact-max update, one exponential per row and block there). */
+int vfa_fp8_attn_noexp_fwd(const void* Q8, const void* K8, const void* Vt8, void* O, float* LSE, int B,
+                           int Hq, int Hkv, int N, int d, int block_m, int block_n, int causal,
+                           int n_sink, int n_local, int use_minit, float softmax_scale, float descale_q,
+                           float descale_k, float descale_v, void* workspace, size_t workspace_bytes,
+                           void* stream);
+
 /* ---- MXFP4 scores: the 4-bit tensor regime of the performance discussion (the "C4" configurations):
  * Q.K^T on operands in the published MX block format (E2M1 elements, two to a byte with the even
  * element in the low nibble, and one E8M0 scale byte 2^(byte - 127) per 32 consecutive features);

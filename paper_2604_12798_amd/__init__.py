@@ -16,7 +16,7 @@ _lib = None
 EXPORTS = ("vfa_workspace_bytes", "vfa_kblock_summary", "vfa_kblock_summary_mode", "fa_baseline_fwd",
            "fa_lazy_rescale_fwd", "fa_lazy_rescale_softexp_fwd", "vfa_attn_fwd", "vsa_attn_fwd", "vfa_variant_fwd", "vfa_kblock_summary_append",
            "vfa_decode_workspace_bytes", "vfa_decode_fwd", "vfa_kblock_summary_append_varlen", "vfa_decode_varlen_fwd", "vfa_fp8_quantize", "vfa_fp8_v_bytes", "vfa_fp8_pack_v",
-           "vfa_fp8_attn_fwd", "vfa_mxfp4_quantize", "vfa_mxfp4_workspace_bytes", "vfa_mxfp4_attn_fwd", "vfa_strerror")
+           "vfa_fp8_attn_fwd", "vfa_fp8_attn_noexp_fwd", "vfa_mxfp4_quantize", "vfa_mxfp4_workspace_bytes", "vfa_mxfp4_attn_fwd", "vfa_strerror")
 
 
 class VfaError(RuntimeError):
@@ -57,6 +57,8 @@ def lib() -> ctypes.CDLL:
         L.vfa_fp8_v_bytes.argtypes = [i, i, i]
         L.vfa_fp8_pack_v.restype = i
         L.vfa_fp8_pack_v.argtypes = [vp, vp, i, i, i, i, f, vp]
+        L.vfa_fp8_attn_noexp_fwd.restype = i
+        L.vfa_fp8_attn_noexp_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, i, i, f, f, f, f, vp, sz, vp]
         L.vfa_mxfp4_quantize.restype = i
         L.vfa_mxfp4_quantize.argtypes = [vp, vp, vp, ctypes.c_longlong, f, vp]
         L.vfa_mxfp4_workspace_bytes.restype = sz
@@ -324,7 +326,8 @@ def fp8_pack_v(V, inv_scale: float, stream=None):
 
 def fp8_attn_fwd(Q8, K8, Vt8, *, descale_q, descale_k, descale_v, frozen=True, block_m=128, block_n=64, causal=True,
                  n_sink=1, n_local=1, use_minit=True, softmax_scale=0.0, workspace=None, out=None, lse=None,
-                 want_lse=True, stream=None):
+                 want_lse=True, stream=None, noexp=False):
+    """E4M3 attention; noexp=True calls vfa_fp8_attn_noexp_fwd (Alg. 1 with the weights' codes taken from the scores)."""
     import torch
     B, Hq, N, d = Q8.shape
     Hkv = K8.shape[1]
@@ -332,12 +335,15 @@ def fp8_attn_fwd(Q8, K8, Vt8, *, descale_q, descale_k, descale_v, frozen=True, b
     L = lse if (lse is not None or not want_lse) else torch.empty((B, Hq, N), dtype=torch.float32, device=Q8.device)
     need = B * Hkv * (-(-N // block_n)) * 128
     ws = torch.empty(max(need, 256), dtype=torch.uint8, device=Q8.device) if workspace is None else workspace
-    rc = lib().vfa_fp8_attn_fwd(int(bool(frozen)), _ptr(Q8), _ptr(K8), _ptr(Vt8), _ptr(O), _ptr(L), B, Hq, Hkv, N, d, block_m,
-                                block_n, int(bool(causal)), int(n_sink), int(n_local), int(use_minit), float(softmax_scale),
-                                float(descale_q), float(descale_k), float(descale_v), _ptr(ws),
-                                ws.numel() * ws.element_size(), _stream(stream))
+    tail = (B, Hq, Hkv, N, d, block_m, block_n, int(bool(causal)), int(n_sink), int(n_local), int(use_minit),
+            float(softmax_scale), float(descale_q), float(descale_k), float(descale_v), _ptr(ws),
+            ws.numel() * ws.element_size(), _stream(stream))
+    if noexp:
+        rc = lib().vfa_fp8_attn_noexp_fwd(_ptr(Q8), _ptr(K8), _ptr(Vt8), _ptr(O), _ptr(L), *tail)
+    else:
+        rc = lib().vfa_fp8_attn_fwd(int(bool(frozen)), _ptr(Q8), _ptr(K8), _ptr(Vt8), _ptr(O), _ptr(L), *tail)
     if rc != 0:
-        raise VfaError(rc, "vfa_fp8_attn_fwd")
+        raise VfaError(rc, "vfa_fp8_attn_noexp_fwd" if noexp else "vfa_fp8_attn_fwd")
     return O, L
 
 

@@ -39,34 +39,56 @@ __device__ __forceinline__ f32x16 mfma_f8(const i32x8& a, const i32x8& b, const 
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, scale_a, 0, 0x7f7f7f7f);
 }
 
+// a wave-uniform pointer as two scalar registers (the compiler cannot always see that it is uniform)
+__device__ __forceinline__ uint64_t uniform_ptr(const void* ptr) {
+    const uint64_t b64 = (uint64_t)(uintptr_t)ptr;
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)b64);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(b64 >> 32));
+    return ((uint64_t)hi << 32) | (uint64_t)lo;
+}
+
+// one LDS-direct load: lane l's 16 (BYTES = 16) or 4 bytes at base + off go to LDS address lds_addr + BYTES * l.
+// Scalar base plus a 32-bit lane offset: one address register per lane instead of a 64-bit pointer.
+template <int BYTES>
+__device__ __forceinline__ void lds_dma(uint64_t base, uint32_t off, uint32_t lds_addr) {
+    uint32_t m0_save;
+    if (BYTES == 16)
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
+                     : "=&s"(m0_save)
+                     : "s"(lds_addr), "v"(off), "s"(base)
+                     : "memory");
+    else
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %2, %3\n\ts_mov_b32 m0, %0"
+                     : "=&s"(m0_save)
+                     : "s"(lds_addr), "v"(off), "s"(base)
+                     : "memory");
+}
+
 // K tile (IS_V = false: rows of 128 bytes from a row-major [*, 128] array, rows clamped to row_limit - 1)
-// or V^T tile (IS_V = true: a contiguous 8 KiB block) -> LDS, 8 one-KiB pieces shared by NWAVES waves
+// or V^T tile (IS_V = true: a contiguous 8 KiB block) -> LDS, 8 one-KiB pieces shared by NWAVES waves.
+// base is the same for all lanes of the wave.
 template <bool IS_V, int NWAVES>
 __device__ __forceinline__ void load_tile8(const uint8_t* base, int first_row, int row_limit, uint8_t* dst, int wave,
                                            int lane) {
     constexpr int NI = 8 / NWAVES;
+    const uint64_t sb = uniform_ptr(base);
 #pragma unroll
     for (int u = 0; u < NI; ++u) {
         const int q = u * NWAVES + wave;
         int r, c;
-        const uint8_t* src;
+        uint32_t off;
         if (IS_V) {
             r = 16 * q + (lane >> 2);
             c = (lane & 3) ^ ((r >> 2) & 3);
-            src = base + r * 64 + c * 16;
+            off = (uint32_t)(r * 64 + c * 16);
         } else {
             r = 8 * q + (lane >> 3);
             c = (lane & 7) ^ ((r >> 1) & 7);
-            src = base + (size_t)min(first_row + r, row_limit - 1) * 128 + c * 16;
+            off = (uint32_t)min(first_row + r, row_limit - 1) * 128u + (uint32_t)(c * 16);
         }
         const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
             (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)(dst + q * 1024));
-        uint32_t m0_save;
-        asm volatile(
-            "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
-            : "=&s"(m0_save)
-            : "s"(lds_addr), "v"(src)
-            : "memory");
+        lds_dma<16>(sb, off, lds_addr);
     }
 }
 
@@ -77,8 +99,24 @@ __device__ __forceinline__ i32x8 lds_frag8(const uint8_t* a0, const uint8_t* a1)
 
 // S^T tile from an E4M3 K tile: st[t][i] as in qk_tile: products of the codes' values times the power of
 // two in scale_a, plus *start (a value per lane, i.e. per query, already spread over 16 registers) if given
+// (NARROW: two fragments in flight instead of four, for a kernel that is short of registers)
+template <bool NARROW = false>
 __device__ __forceinline__ void qk_tile8(const uint8_t* kt, const i32x8* qf, f32x16* st, int ql, int hh,
                                          int scale_a = 0x7f7f7f7f, const f32x16* start = nullptr) {
+    if (NARROW) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            i32x8 g[2];
+#pragma unroll
+            for (int kh = 0; kh < 2; ++kh) {
+                const int row = 32 * t + ql, c0 = 4 * kh + 2 * hh;
+                g[kh] = lds_frag8(kt + Tile8::k_off(row, c0), kt + Tile8::k_off(row, c0 + 1));
+            }
+            st[t] = mfma_f8(g[0], qf[0], start ? *start : f32x16{0}, scale_a);
+            st[t] = mfma_f8(g[1], qf[1], st[t], scale_a);
+        }
+        return;
+    }
     i32x8 f[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {  // e = 2 t + kh
@@ -91,9 +129,27 @@ __device__ __forceinline__ void qk_tile8(const uint8_t* kt, const i32x8* qf, f32
 }
 
 // P_BF8: the P operand holds E5M2 codes (V stays E4M3)
-template <bool P_BF8 = false>
+template <bool P_BF8 = false, bool NARROW = false>
 __device__ __forceinline__ void pv_tile8(const uint8_t* vt, const uint32_t* pk, f32x16* ot, int lane, int hh) {
     const i32x8 pf = {(int)pk[0], (int)pk[1], (int)pk[2], (int)pk[3], (int)pk[4], (int)pk[5], (int)pk[6], (int)pk[7]};
+    if (NARROW) {  // two fragments in flight instead of four
+#pragma unroll
+        for (int d2 = 0; d2 < 2; ++d2) {
+            i32x8 g[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int row = 32 * (2 * d2 + u) + (lane & 31);
+                g[u] = lds_frag8(vt + Tile8::v_off(row, 2 * hh), vt + Tile8::v_off(row, 2 * hh + 1));
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int db = 2 * d2 + u;
+                ot[db] = P_BF8 ? __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(g[u], pf, ot[db], 0, 1, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f)
+                               : mfma_f8(g[u], pf, ot[db]);
+            }
+        }
+        return;
+    }
     i32x8 f[4];
 #pragma unroll
     for (int db = 0; db < 4; ++db) {
@@ -185,6 +241,69 @@ __device__ __forceinline__ void softmax_tile8_folded(f32x16* st, uint32_t* pk, f
         }
 }
 
+// ---- Alg. 1 without exponentials (NOEXP).  The code of a small float read as an integer is a piecewise-linear
+// logarithm: an E5M2 code c = 4 E + m stands for 2^(E - 15) (1 + m / 4), the chord approximation of
+// 2^(c / 4 - 15), never more than 6.15 % above it.  So when a score arrives as x = s - m - H in log2 units, the
+// code of exp2(x) 2^15 is, up to that chord error and the rounding to a quarter of a binade, just
+// round(4 x + 120): a multiply-add and a float-to-byte conversion.  The multiply (4 = 2^2) goes into the MFMA's
+// block scale and the add into its accumulator start (the frozen max is known before the tile), so a frozen
+// tile's scores leave the matrix unit AS CODES: what is left per score is a clamp to the largest finite code and
+// v_cvt_pk_u8_f32 (round to nearest even, saturating at 0: measured).  The offset is lowered by
+// 4 log2(1.0303) = 0.1723 to centre the chord error: weight / exact weight lies in [0.89, 1.12] (the format's
+// own rounding would give +-12.5 %).  E5M2 rather than E4M3 because the window has to hold, below the frozen max,
+// the headroom, the overshoot of the seed and the spread of the row, and E4M3's subnormal codes, which the
+// rounded-exponential path leans on for its last three binades, are not logarithmic.  The row sum comes from
+// the same rounded weights through one more MFMA (a block of ones times P), so O = sum(w v) / sum(w) is a properly
+// normalised average under weights that are each within 12 % of the exact ones; LSE inherits that error.
+constexpr float kCodeOffset = 119.8277f;  // 4 * (15 + 15) - 0.1723
+constexpr float kMaxCode = 123.f;          // 0x7B = 57344, the largest finite E5M2 value
+constexpr float kCodesPerBinade = 4.f;
+
+template <bool MASKED>
+__device__ __forceinline__ void codes_tile8(f32x16* st, uint32_t* pk, int key0, int limit, int hh, float add = 0.f) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; r += 4) {
+            uint32_t w = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float c = __builtin_amdgcn_fmed3f(st[t][r + e] + add, 0.f, kMaxCode);  // (fminf would first quiet a NaN)
+                if (MASKED) c = (32 * t + 8 * ((r + e) >> 2) + ((r + e) & 3) <= limit - key0 - 4 * hh) ? c : 0.f;
+                w = __builtin_amdgcn_cvt_pk_u8_f32(c, e, w);
+            }
+            pk[4 * t + (r >> 2)] = w;
+        }
+}
+
+// exact-max tile of the NOEXP form: st holds 4 * (log2-domain scores); row max, rescale of ot and of the row-sum
+// block lt, then codes relative to the new max
+template <bool MASKED>
+__device__ __forceinline__ void special_tile8_noexp(f32x16* st, uint32_t* pk, f32x16* ot, f32x16& lt, float& m2, float headroom,
+                                                    int key0, int limit, int hh) {
+    if (MASKED) {
+        const int rel = limit - key0 - 4 * hh;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) st[t][r] = (32 * t + 8 * (r >> 2) + (r & 3) <= rel) ? st[t][r] : -INFINITY;
+    }
+    const float mx = tile_rowmax<false>(st, 0, 0, hh);
+    const float m_new = fmaxf(m2, xhalf_max(mx) * (1.f / kCodesPerBinade));
+    const float msub = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m2 - msub);
+    lt *= alpha;
+#pragma unroll
+    for (int db = 0; db < 4; ++db) ot[db] *= alpha;
+    m2 = m_new;
+    const float sub = kCodesPerBinade * (msub + headroom) - kCodeOffset;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st[t][r] -= sub;   // (-inf stays -inf: code 0)
+    codes_tile8<false>(st, pk, 0, 0, hh);
+}
+
 struct Fp8Params {
     const uint8_t* Q;      // [B, Hq, N, 128] E4M3
     const uint8_t* K;      // [B, Hkv, N, 128]
@@ -205,9 +324,10 @@ struct Fp8Params {
 // FOLD (Alg. 1 only, when the factor between code products and log2-domain scores is a power of two): the
 // K operand's block scale applies it inside every Q.K^T MFMA, and on frozen tiles the accumulators start at
 // -(m + H), so the scores come out of the matrix unit ready for exp2.
-template <int MODE, bool FOLD>
+template <int MODE, bool FOLD, bool NOEXP = false>
 __global__ __launch_bounds__(256, FOLD ? 3 : 2) void attn_fp8_kernel(const Fp8Params p) {
     static_assert(!FOLD || MODE == MODE_VFA, "folding needs a max that is known before the tile");
+    static_assert(!NOEXP || FOLD, "codes straight from the matrix unit need the scale and the max folded into it");
     const int sa = FOLD ? p.scale_a : 0x7f7f7f7f;
     constexpr int D = 128, BM = 128, DB = 4;
     __shared__ __attribute__((aligned(16))) uint8_t smem[2 * (Tile8::KBYTES + Tile8::VBYTES)];
@@ -281,6 +401,8 @@ __global__ __launch_bounds__(256, FOLD ? 3 : 2) void attn_fp8_kernel(const Fp8Pa
         wait_vm0_and_sync();
     }
     f32x16 start;  // FOLD: -(m + H) of this lane's query in all 16 registers, set once the max is frozen
+    float code0 = 0.f;  // NOEXP: code offset - 4 (m + H), added on the vector side (16 registers matter more than 32 adds)
+    f32x16 lt = {0};  // NOEXP: 32 copies of this lane's row sum of the rounded weights (times 2^15)
     // One visit; SPECIAL and MASKED are compile-time so that each of the three loops below has one softmax body.
     auto visit = [&](int k, auto special_c, auto masked_c) __attribute__((always_inline)) {
         constexpr bool SPECIAL = decltype(special_c)::value, MASKED = decltype(masked_c)::value;
@@ -293,14 +415,25 @@ __global__ __launch_bounds__(256, FOLD ? 3 : 2) void attn_fp8_kernel(const Fp8Pa
         f32x16 st[2];
         uint32_t pk[8];
         __builtin_amdgcn_s_setprio(1);
-        if (FOLD && !SPECIAL) qk_tile8(Ks + buf * Tile8::KBYTES, qf, st, ql, hh, sa, &start);
+        if (NOEXP) qk_tile8<true>(Ks + buf * Tile8::KBYTES, qf, st, ql, hh, sa);
+        else if (FOLD && !SPECIAL) qk_tile8(Ks + buf * Tile8::KBYTES, qf, st, ql, hh, sa, &start);
         else qk_tile8(Ks + buf * Tile8::KBYTES, qf, st, ql, hh, sa);
         __builtin_amdgcn_s_setprio(0);
         const bool needs_mask = (p.causal && j * BN + BN - 1 > row0) || (j + 1) * BN > N;
-        if (FOLD && !SPECIAL) softmax_tile8_folded<MASKED>(st, pk, lsum, j * BN, needs_mask ? limit : 0x3fffffff, hh);
+        if (NOEXP && !SPECIAL) codes_tile8<MASKED>(st, pk, j * BN, needs_mask ? limit : 0x3fffffff, hh, code0);
+        else if (NOEXP) special_tile8_noexp<MASKED>(st, pk, ot, lt, m2, p.headroom, j * BN, needs_mask ? limit : 0x3fffffff, hh);
+        else if (FOLD && !SPECIAL) softmax_tile8_folded<MASKED>(st, pk, lsum, j * BN, needs_mask ? limit : 0x3fffffff, hh);
         else softmax_tile8<SPECIAL, MASKED>(st, pk, ot, m2, lsum, p.c, p.headroom, j * BN, needs_mask ? limit : 0x3fffffff, hh);
         __builtin_amdgcn_s_setprio(1);
-        pv_tile8(Vs + buf * Tile8::VBYTES, pk, ot, lane, hh);
+        pv_tile8<NOEXP, NOEXP>(Vs + buf * Tile8::VBYTES, pk, ot, lane, hh);
+        if (NOEXP) {
+            // row sums of the rounded weights: a block of ones times P (E5M2).  The ones are E2M1 (1.0 = code 2): a
+            // 4-bit operand takes four registers instead of eight, and with all elements equal the different order of
+            // the k index in 4-bit and 8-bit operands does not matter
+            const i32x8 ones = {0x22222222, 0x22222222, 0x22222222, 0x22222222, 0, 0, 0, 0};
+            const i32x8 pf = {(int)pk[0], (int)pk[1], (int)pk[2], (int)pk[3], (int)pk[4], (int)pk[5], (int)pk[6], (int)pk[7]};
+            lt = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ones, pf, lt, 4, 1, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+        }
         __builtin_amdgcn_s_setprio(0);
         wait_vm0_and_sync();
     };
@@ -322,14 +455,16 @@ __global__ __launch_bounds__(256, FOLD ? 3 : 2) void attn_fp8_kernel(const Fp8Pa
     for (; k < n_lead; ++k) visit(k, true_type{}, true_type{});
     if (FOLD) {
         const float v = -(m2 + p.headroom);
+        if (NOEXP) code0 = kCodeOffset + kCodesPerBinade * v;
 #pragma unroll
         for (int r = 0; r < 16; ++r) start[r] = v;
     }
     for (; k < k_fast_end; ++k) visit(k, std::integral_constant<bool, TAIL_SPECIAL>{}, false_type{});
     for (; k < vis.total; ++k) visit(k, std::integral_constant<bool, TAIL_SPECIAL>{}, true_type{});
     // O = descale_v * 2^-8 * O^T / l (the codes of P carry 2^8); LSE = (m2 + H + log2 l) ln 2  (l sums exp2(s c - m2 - H))
-    const float l = xhalf_sum(lsum);
-    const float inv = l > 0.f ? p.descale_v * 0.00390625f / l : 0.f;
+    // (NOEXP: every register of lt holds the whole row sum, with the same 2^15 as the numerator)
+    const float l = NOEXP ? lt[0] * 0x1p-15f : xhalf_sum(lsum);
+    const float inv = l > 0.f ? p.descale_v * (NOEXP ? 0x1p-15f : 0x1p-8f) / l : 0.f;
     if (qrow < N) {
         uint16_t* Og = p.O + ((size_t)(b * p.Hq + h) * N + qrow) * D;
 #pragma unroll

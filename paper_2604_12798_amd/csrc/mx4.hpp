@@ -128,32 +128,22 @@ __device__ __forceinline__ int spread_byte(uint32_t x, uint32_t n) {
 }
 
 // 64 dwords (the four scale bytes of rows first_row .. first_row + 63 of a row-major [*, 4] array, rows clamped
-// to row_limit - 1) -> LDS, by one wave
+// to row_limit - 1) -> LDS, by one wave; base is the same for all lanes
 __device__ __forceinline__ void load_scales64(const uint8_t* base, int first_row, int row_limit, uint32_t* dst, int lane) {
-    const uint8_t* src = base + (size_t)min(first_row + lane, row_limit - 1) * 4;
     const uint32_t lds_addr =
         __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t*)dst);
-    uint32_t m0_save;
-    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %2, off\n\ts_mov_b32 m0, %0"
-                 : "=&s"(m0_save)
-                 : "s"(lds_addr), "v"(src)
-                 : "memory");
+    lds_dma<4>(uniform_ptr(base), (uint32_t)min(first_row + lane, row_limit - 1) * 4u, lds_addr);
 }
 
 // MXFP4 K tile (64 rows of 64 bytes from a row-major [*, 64] array, rows clamped) -> LDS: four one-KiB pieces,
-// one per wave
+// one per wave; base is the same for all lanes
 __device__ __forceinline__ void load_tile4(const uint8_t* base, int first_row, int row_limit, uint8_t* dst, int wave,
                                            int lane) {
     const int r = 16 * wave + (lane >> 2);
     const int c = (lane & 3) ^ ((r >> 2) & 3);
-    const uint8_t* src = base + (size_t)min(first_row + r, row_limit - 1) * 64 + c * 16;
     const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
         (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)(dst + wave * 1024));
-    uint32_t m0_save;
-    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
-                 : "=&s"(m0_save)
-                 : "s"(lds_addr), "v"(src)
-                 : "memory");
+    lds_dma<16>(uniform_ptr(base), (uint32_t)min(first_row + r, row_limit - 1) * 64u + (uint32_t)(c * 16), lds_addr);
 }
 
 // S^T tile from an MXFP4 K tile and its scales: st[t][i] as in qk_tile, in units of the dequantised products

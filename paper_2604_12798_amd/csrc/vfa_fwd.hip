@@ -391,10 +391,14 @@ int vfa_fp8_pack_v(const void* V, void* Vt, int B, int Hkv, int N, int d, float 
     return hipGetLastError() == hipSuccess ? VFA_OK : VFA_ERR_HIP;
 }
 
-int vfa_fp8_attn_fwd(int frozen, const void* Q8, const void* K8, const void* Vt8, void* O, float* LSE, int B, int Hq, int Hkv,
-                     int N, int d, int block_m, int block_n, int causal, int n_sink, int n_local, int use_minit,
-                     float softmax_scale, float descale_q, float descale_k, float descale_v, void* workspace,
-                     size_t workspace_bytes, void* stream) {
+}  // extern "C"
+
+namespace {
+
+int fp8_common(int frozen, bool noexp, const void* Q8, const void* K8, const void* Vt8, void* O, float* LSE, int B, int Hq,
+               int Hkv, int N, int d, int block_m, int block_n, int causal, int n_sink, int n_local, int use_minit,
+               float softmax_scale, float descale_q, float descale_k, float descale_v, void* workspace,
+               size_t workspace_bytes, void* stream) {
     if (B < 0 || N < 0 || Hq <= 0 || Hkv <= 0 || d <= 0 || block_m <= 0 || block_n <= 0) return VFA_ERR_INVALID_ARG;
     if (Hq % Hkv != 0 || (frozen != 0 && frozen != 1)) return VFA_ERR_INVALID_ARG;
     if (!(descale_q > 0.f && descale_k > 0.f && descale_v > 0.f) || !isfinite(descale_q * descale_k) || !isfinite(descale_v) ||
@@ -437,15 +441,39 @@ int vfa_fp8_attn_fwd(int frozen, const void* Q8, const void* K8, const void* Vt8
         const float mant = frexpf(p.c, &ex);  // p.c = mant * 2^ex, mant in [0.5, 1)
         if (fabsf(mant - 0.5f) <= 0x1p-18f && ex - 1 >= -100 && ex - 1 <= 100) {
             fold = true;
-            p.scale_a = (127 + ex - 1) * 0x01010101;
-            p.c = 1.f;
+            // (the form without exponentials takes its scores times 4: two more in the exponent byte, and the
+            // factor that turns a raw row max into log2 units becomes 1/4)
+            p.scale_a = (127 + ex - 1 + (noexp ? 2 : 0)) * 0x01010101;
+            p.c = noexp ? 0.25f : 1.f;
         }
     }
+    if (noexp && !fold) return VFA_ERR_INVALID_ARG;
     const dim3 grid((unsigned)(B * Hq * Tr));
-    if (fold) attn_fp8_kernel<MODE_VFA, true><<<grid, 256, 0, s>>>(p);
+    if (noexp) attn_fp8_kernel<MODE_VFA, true, true><<<grid, 256, 0, s>>>(p);
+    else if (fold) attn_fp8_kernel<MODE_VFA, true><<<grid, 256, 0, s>>>(p);
     else if (frozen) attn_fp8_kernel<MODE_VFA, false><<<grid, 256, 0, s>>>(p);
     else attn_fp8_kernel<MODE_FA, false><<<grid, 256, 0, s>>>(p);
     return hipGetLastError() == hipSuccess ? VFA_OK : VFA_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int vfa_fp8_attn_fwd(int frozen, const void* Q8, const void* K8, const void* Vt8, void* O, float* LSE, int B, int Hq, int Hkv,
+                     int N, int d, int block_m, int block_n, int causal, int n_sink, int n_local, int use_minit,
+                     float softmax_scale, float descale_q, float descale_k, float descale_v, void* workspace,
+                     size_t workspace_bytes, void* stream) {
+    return fp8_common(frozen, false, Q8, K8, Vt8, O, LSE, B, Hq, Hkv, N, d, block_m, block_n, causal, n_sink, n_local, use_minit,
+                      softmax_scale, descale_q, descale_k, descale_v, workspace, workspace_bytes, stream);
+}
+
+int vfa_fp8_attn_noexp_fwd(const void* Q8, const void* K8, const void* Vt8, void* O, float* LSE, int B, int Hq, int Hkv, int N,
+                           int d, int block_m, int block_n, int causal, int n_sink, int n_local, int use_minit,
+                           float softmax_scale, float descale_q, float descale_k, float descale_v, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+    return fp8_common(1, true, Q8, K8, Vt8, O, LSE, B, Hq, Hkv, N, d, block_m, block_n, causal, n_sink, n_local, use_minit,
+                      softmax_scale, descale_q, descale_k, descale_v, workspace, workspace_bytes, stream);
 }
 
 size_t vfa_mxfp4_workspace_bytes(int B, int Hkv, int N) {

@@ -190,3 +190,34 @@ def test_fp8_full_size_sampled_blocks(vfa, oracle):
         print("cfg3 fp8", "frozen" if frozen else "online", "max_abs %.4f mean_abs %.5f lse %.2e" % (err.max(), err.mean(), lerr), flush=True)
         assert not np.isnan(got_O).any()
         assert err.max() <= vmax / 16 * 1.05 + 2e-2 and err.mean() <= vmax / 16 / 8 and lerr <= LSE_ABS
+
+
+@pytest.mark.parametrize("name,w", SHAPES, ids=[s[0] for s in SHAPES])
+def test_fp8_noexp_matches_oracle_within_the_code_error(vfa, oracle, name, w):
+    """Alg. 1 with the weights' E5M2 codes taken straight from the scores (no exponential): every weight is within
+    [0.89, 1.12] of the exact one and the row sum uses the same weights, so with eps = 0.12
+    |O - O_exact| <= 2 eps / (1 - eps) max|V| in the worst case (two keys with opposite V and opposite errors; plus the
+    bf16 output) and |LSE - LSE_exact| <= -ln 0.89 = 0.117; typical rows average the errors out."""
+    import torch
+    pr = quantised_problem(vfa, oracle, w, fold=True)
+    blocks = wl.all_blocks(w)
+    Oe, Le, Me = oracle.exact(pr["Qd"], pr["Kd"], pr["Vd"], w.block_m, w.causal, blocks)
+    vmax = float(np.abs(pr["Vd"]).max())
+    kw = dict(descale_k=pr["sk"], descale_v=pr["sv"], block_m=w.block_m, block_n=w.block_n, causal=w.causal,
+              n_sink=w.n_sink, n_local=w.n_local)
+    O, L = vfa.fp8_attn_fwd(pr["Q8"], pr["K8"], pr["Vt8"], descale_q=pr["sq"], noexp=True, **kw)
+    torch.cuda.synchronize()
+    got_O, got_L = gather_blocks(O, blocks, w.block_m, w.N), gather_blocks(L, blocks, w.block_m, w.N)
+    valid = ~np.isnan(Le)
+    assert not np.isnan(got_O[valid]).any()
+    err = np.abs(got_O[valid] - Oe[valid])
+    lerr = got_L[valid] - Le[valid]
+    eps = 0.12
+    print(name, "noexp max_abs %.4f mean_abs %.5f lse err min %.4f max %.4f mean |.| %.4f (worst-case bound %.3f)" %
+          (err.max(), err.mean(), lerr.min(), lerr.max(), np.abs(lerr).mean(), 2 * eps / (1 - eps) * vmax), flush=True)
+    assert err.max() <= vmax / 8 * 1.05 + 2e-2             # in practice inside the bar of properly rounded E5M2 weights
+    assert err.mean() <= vmax / 8 / 8
+    assert -0.12 <= lerr.min() and lerr.max() <= 0.12
+    # a scale that is not a power of two cannot be folded into the matrix instruction: refused, not approximated
+    with pytest.raises(vfa.VfaError):
+        vfa.fp8_attn_fwd(pr["Q8"], pr["K8"], pr["Vt8"], descale_q=pr["sq"] * 1.01, noexp=True, **kw)
