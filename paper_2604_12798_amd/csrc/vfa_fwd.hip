@@ -418,11 +418,6 @@ int fp8_common(int frozen, bool noexp, const void* Q8, const void* K8, const voi
     const bool minit = frozen && use_minit;
     if (minit && (!workspace || !aligned16(workspace) || workspace_bytes < (size_t)B * Hkv * Tc * 128)) return VFA_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
-    (void)hipGetLastError();
-    if (minit && use_minit == 1) {
-        fp8_kblock_summary_kernel<<<dim3((unsigned)Tc, (unsigned)(B * Hkv)), 256, 0, s>>>((const uint8_t*)K8, (uint8_t*)workspace, N, Tc);
-        if (hipGetLastError() != hipSuccess) return VFA_ERR_HIP;
-    }
     Fp8Params p{};
     p.Q = (const uint8_t*)Q8; p.K = (const uint8_t*)K8; p.Vt = (const uint8_t*)Vt8; p.Krepr = (const uint8_t*)workspace;
     p.O = (uint16_t*)O; p.LSE = LSE;
@@ -447,7 +442,12 @@ int fp8_common(int frozen, bool noexp, const void* Q8, const void* K8, const voi
             p.c = noexp ? 0.25f : 1.f;
         }
     }
-    if (noexp && !fold) return VFA_ERR_INVALID_ARG;
+    if (noexp && !fold) return VFA_ERR_INVALID_ARG;  // (before anything is launched)
+    (void)hipGetLastError();
+    if (minit && use_minit == 1) {
+        fp8_kblock_summary_kernel<<<dim3((unsigned)Tc, (unsigned)(B * Hkv)), 256, 0, s>>>((const uint8_t*)K8, (uint8_t*)workspace, N, Tc);
+        if (hipGetLastError() != hipSuccess) return VFA_ERR_HIP;
+    }
     const dim3 grid((unsigned)(B * Hq * Tr));
     if (noexp) attn_fp8_kernel<MODE_VFA, true, true><<<grid, 256, 0, s>>>(p);
     else if (fold) attn_fp8_kernel<MODE_VFA, true><<<grid, 256, 0, s>>>(p);

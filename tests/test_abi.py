@@ -120,6 +120,12 @@ def test_bad_arguments_are_rejected_before_launch(pkg):
     assert f8(0, p, p, p, p, none, 1, 4, 2, 256, 64, 128, 64, 1, 1, 1, 1, 0.0, 1.0, 1.0, 1.0, p, 1 << 20, none) == -2   # d = 64
     assert f8(0, none, p, p, p, none, *f8shape, 1, 1, 1, 0.0, 1.0, 1.0, 1.0, p, 1 << 20, none) == -1
     assert f8(0, p, p, p, p, none, 0, 4, 2, 256, 128, 128, 64, 1, 1, 1, 1, 0.0, 1.0, 1.0, 1.0, none, 0, none) == 0
+    nx = lambda *a: L.vfa_fp8_attn_noexp_fwd(*a)
+    # descale_q * descale_k * scale * log2(e): 2^-3.5 * log2(e) is no power of two -> refused before any launch
+    assert nx(p, p, p, p, none, *f8shape, 1, 1, 1, 0.0, 1.0, 1.0, 1.0, p, 1 << 20, none) == -1
+    assert nx(p, p, p, p, none, *f8shape, 1, 1, 1, 0.0, 1.0, 1.0, 1.0, none, 0, none) == -1            # workspace missing
+    assert nx(none, p, p, p, none, *f8shape, 1, 1, 1, 0.0, 1.0, 1.0, 1.0, p, 1 << 20, none) == -1
+    assert nx(p, p, p, p, none, 0, 4, 2, 256, 128, 128, 64, 1, 1, 1, 1, 0.0, 1.0, 1.0, 1.0, none, 0, none) == 0
     m4 = lambda *a: L.vfa_mxfp4_attn_fwd(*a)
     # frozen, Q4, QS, K4, KS, Vt8, O, LSE, shape, n_sink, n_local, use_minit, softmax_scale, descale_v, workspace, bytes, stream
     assert m4(1, p, p, p, p, p, p, none, *f8shape, 1, 1, 1, 0.0, 1.0, none, 0, none) == -1             # summaries need a workspace
