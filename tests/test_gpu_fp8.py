@@ -221,3 +221,17 @@ def test_fp8_noexp_matches_oracle_within_the_code_error(vfa, oracle, name, w):
     # a scale that is not a power of two cannot be folded into the matrix instruction: refused, not approximated
     with pytest.raises(vfa.VfaError):
         vfa.fp8_attn_fwd(pr["Q8"], pr["K8"], pr["Vt8"], descale_q=pr["sq"] * 1.01, noexp=True, **kw)
+
+
+def test_fp8_noexp_frozen_max_far_too_low_is_capped_not_nan(vfa, oracle):
+    """No m-init and a single local block: rows whose maximum lies in a far (frozen) tile exceed the headroom; their
+    codes are clamped to the largest finite one, so the result is not exact but stays finite and normalised."""
+    import torch
+    w = W("cfg4", B=1, Hq=2, Hkv=2, N=2048)
+    pr = quantised_problem(vfa, oracle, w, fold=True)
+    O, L = vfa.fp8_attn_fwd(pr["Q8"], pr["K8"], pr["Vt8"], noexp=True, use_minit=False, n_sink=1, n_local=1,
+                            descale_q=pr["sq"], descale_k=pr["sk"], descale_v=pr["sv"], causal=False)
+    torch.cuda.synchronize()
+    o = O.float().cpu().numpy()
+    assert np.isfinite(o).all() and np.isfinite(L.cpu().numpy()).all()
+    assert np.abs(o).max() <= float(np.abs(pr["Vd"]).max()) * 1.01
