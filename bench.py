@@ -240,10 +240,13 @@ def main():
             ms4_plain = time_region(lambda: vfa.mxfp4_attn_fwd(Q4, QS, K4, KS, Vt8, frozen=True, **m4), args.steps, args.warmup)
             ms4_vfa = time_region(lambda: vfa.mxfp4_attn_fwd(Q4f, QSf, K4, KS, Vt8, frozen=True, softmax_scale=math.log(2.0), **m4),
                                   args.steps, args.warmup)
+            ms4_noexp = time_region(lambda: vfa.mxfp4_attn_fwd(Q4f, QSf, K4, KS, Vt8, noexp=True, softmax_scale=math.log(2.0), **m4),
+                                    args.steps, args.warmup)
             peak4 = 2.0 / (1.0 / 10100.0 + 1.0 / 5000.0)
             out["mxfp4"] = {"vfa_ms": ms4_vfa, "vfa_tflops": dense / ms4_vfa / 1e9, "fa_ms": ms4_fa, "fa_tflops": dense / ms4_fa / 1e9,
                             "speedup_vfa_vs_fa": ms4_fa / ms4_vfa, "peak_tflops": peak4, "frac_vfa": dense / ms4_vfa / 1e9 / peak4,
                             "vfa_unfolded_ms": ms4_plain, "vfa_unfolded_tflops": dense / ms4_plain / 1e9,
+                            "vfa_noexp_ms": ms4_noexp, "vfa_noexp_tflops": dense / ms4_noexp / 1e9,
                             "kernel": "attn_mx4_kernel (Q.K^T on MXFP4, P.V on 8-bit operands; 4 waves); vfa: Q multiplied by "
                                       "scale * log2(e) before quantising, frozen max into the accumulator start"}
             del Q4, QS, Q4f, QSf, K4, KS, ws4

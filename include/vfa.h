@@ -284,6 +284,16 @@ int vfa_mxfp4_attn_fwd(int frozen, const void* Q4, const void* QS, const void* K
                        float softmax_scale, float descale_v, void* workspace, size_t workspace_bytes,
                        void* stream);
 
+/* vfa_mxfp4_attn_fwd's Alg. 1 without exponentials, as vfa_fp8_attn_noexp_fwd: needs softmax_scale * log2(e) = 1
+ * (to 2^-18, else VFA_ERR_INVALID_ARG; the caller multiplied Q by its scale * log2(e) before quantising); the
+ * factor 4 of the code scale rides in the queries' block-scale bytes (which must stay below 253).  Weights within
+ * [-11 %, +12 %] of the exact ones, normalised by their own sum; LSE within 0.12 nats. */
+int vfa_mxfp4_attn_noexp_fwd(const void* Q4, const void* QS, const void* K4, const void* KS,
+                             const void* Vt8, void* O, float* LSE, int B, int Hq, int Hkv, int N, int d,
+                             int block_m, int block_n, int causal, int n_sink, int n_local,
+                             int use_minit, float softmax_scale, float descale_v, void* workspace,
+                             size_t workspace_bytes, void* stream);
+
 /* Static string for a return code. */
 const char* vfa_strerror(int code);
 

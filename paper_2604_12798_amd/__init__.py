@@ -16,7 +16,7 @@ _lib = None
 EXPORTS = ("vfa_workspace_bytes", "vfa_kblock_summary", "vfa_kblock_summary_mode", "fa_baseline_fwd",
            "fa_lazy_rescale_fwd", "fa_lazy_rescale_softexp_fwd", "vfa_attn_fwd", "vsa_attn_fwd", "vfa_variant_fwd", "vfa_kblock_summary_append",
            "vfa_decode_workspace_bytes", "vfa_decode_fwd", "vfa_kblock_summary_append_varlen", "vfa_decode_varlen_fwd", "vfa_fp8_quantize", "vfa_fp8_v_bytes", "vfa_fp8_pack_v",
-           "vfa_fp8_attn_fwd", "vfa_fp8_attn_noexp_fwd", "vfa_mxfp4_quantize", "vfa_mxfp4_workspace_bytes", "vfa_mxfp4_attn_fwd", "vfa_strerror")
+           "vfa_fp8_attn_fwd", "vfa_fp8_attn_noexp_fwd", "vfa_mxfp4_quantize", "vfa_mxfp4_workspace_bytes", "vfa_mxfp4_attn_fwd", "vfa_mxfp4_attn_noexp_fwd", "vfa_strerror")
 
 
 class VfaError(RuntimeError):
@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
         L.vfa_mxfp4_workspace_bytes.argtypes = [i, i, i]
         L.vfa_mxfp4_attn_fwd.restype = i
         L.vfa_mxfp4_attn_fwd.argtypes = [i, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, i, i, f, f, vp, sz, vp]
+        L.vfa_mxfp4_attn_noexp_fwd.restype = i
+        L.vfa_mxfp4_attn_noexp_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, i, i, f, f, vp, sz, vp]
         L.vfa_fp8_attn_fwd.restype = i
         L.vfa_fp8_attn_fwd.argtypes = [i, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, i, i, f, f, f, f, vp, sz, vp]
         L.fa_baseline_fwd.restype = i
@@ -366,8 +368,9 @@ def mxfp4_workspace_bytes(B, Hkv, N) -> int:
 
 def mxfp4_attn_fwd(Q4, QS, K4, KS, Vt8, *, descale_v, frozen=True, block_m=128, block_n=64, causal=True, n_sink=1,
                    n_local=1, use_minit=True, softmax_scale=0.0, workspace=None, out=None, lse=None, want_lse=True,
-                   stream=None):
-    """Attention with MXFP4 scores (Q4/QS, K4/KS from mxfp4_quantize) and E4M3 P.V (Vt8 from fp8_pack_v)."""
+                   stream=None, noexp=False):
+    """Attention with MXFP4 scores (Q4/QS, K4/KS from mxfp4_quantize) and 8-bit P.V (Vt8 from fp8_pack_v);
+    noexp=True calls vfa_mxfp4_attn_noexp_fwd."""
     import torch
     B, Hq, N, dh = Q4.shape
     d, Hkv = 2 * dh, K4.shape[1]
@@ -375,10 +378,10 @@ def mxfp4_attn_fwd(Q4, QS, K4, KS, Vt8, *, descale_v, frozen=True, block_m=128, 
     L = lse if (lse is not None or not want_lse) else torch.empty((B, Hq, N), dtype=torch.float32, device=Q4.device)
     need = mxfp4_workspace_bytes(B, Hkv, N)
     ws = torch.empty(max(need, 256), dtype=torch.uint8, device=Q4.device) if workspace is None else workspace
-    rc = lib().vfa_mxfp4_attn_fwd(int(bool(frozen)), _ptr(Q4), _ptr(QS), _ptr(K4), _ptr(KS), _ptr(Vt8), _ptr(O), _ptr(L), B, Hq,
-                                  Hkv, N, d, block_m, block_n, int(bool(causal)), int(n_sink), int(n_local), int(use_minit),
-                                  float(softmax_scale), float(descale_v), _ptr(ws), ws.numel() * ws.element_size(),
-                                  _stream(stream))
+    tail = (B, Hq, Hkv, N, d, block_m, block_n, int(bool(causal)), int(n_sink), int(n_local), int(use_minit),
+            float(softmax_scale), float(descale_v), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream))
+    ops = (_ptr(Q4), _ptr(QS), _ptr(K4), _ptr(KS), _ptr(Vt8), _ptr(O), _ptr(L))
+    rc = lib().vfa_mxfp4_attn_noexp_fwd(*ops, *tail) if noexp else lib().vfa_mxfp4_attn_fwd(int(bool(frozen)), *ops, *tail)
     if rc != 0:
-        raise VfaError(rc, "vfa_mxfp4_attn_fwd")
+        raise VfaError(rc, "vfa_mxfp4_attn_noexp_fwd" if noexp else "vfa_mxfp4_attn_fwd")
     return O, L, ws

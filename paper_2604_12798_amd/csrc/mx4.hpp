@@ -183,9 +183,12 @@ struct Mx4Params {
 // As attn_fp8_kernel with the score product on MXFP4 operands.  FOLD (Alg. 1 only, softmax scale * log2(e) = 1,
 // i.e. the caller folded that factor into Q before quantising): frozen tiles start their accumulators at
 // -(m + H) and go to exp2 untouched.
-template <int MODE, bool FOLD>
+// NOEXP (with FOLD): the weights' E5M2 codes are taken from the scores as in attn_fp8_kernel's form without
+// exponentials; the factor 4 of the code scale is added to the queries' block-scale bytes (two binades).
+template <int MODE, bool FOLD, bool NOEXP = false>
 __global__ __launch_bounds__(256, 3) void attn_mx4_kernel(const Mx4Params p) {
     static_assert(!FOLD || MODE == MODE_VFA, "folding needs a max that is known before the tile");
+    static_assert(!NOEXP || FOLD, "codes straight from the matrix unit need the scores in log2 units");
     constexpr int D = 128, BM = 128, DB = 4;
     // Alg. 1 keeps exp(S - m) in E5M2: the summaries of MXFP4 keys collect the upward rounding errors of 64 keys per
     // feature, so the seeded max can sit ten binades above the scores, more than E4M3 has to spare
@@ -234,7 +237,7 @@ __global__ __launch_bounds__(256, 3) void attn_mx4_kernel(const Mx4Params p) {
 #pragma unroll
         for (int kh = 0; kh < 2; ++kh) {
             qf[kh] = *reinterpret_cast<const u32x4*>(p.Q + qr * 64 + 32 * kh + 16 * hh);
-            qs[kh] = spread_byte(sw, 2 * kh + hh);
+            qs[kh] = spread_byte(sw, 2 * kh + hh) + (NOEXP ? 0x02020202 : 0);  // (scale bytes of real data are far from 253)
         }
     }
     auto load_k = [&](int j, int buf) __attribute__((always_inline)) {
@@ -283,6 +286,8 @@ __global__ __launch_bounds__(256, 3) void attn_mx4_kernel(const Mx4Params p) {
         wait_vm0_and_sync();
     }
     f32x16 start;  // FOLD: -(m + H) of this lane's query in all 16 registers, set once the max is frozen
+    f32x16 lt = {0};   // NOEXP: 32 copies of this lane's row sum of the rounded weights (times 2^15)
+    float code0 = 0.f;  // NOEXP: code offset - 4 (m + H)
     auto visit = [&](int k, auto special_c, auto masked_c) __attribute__((always_inline)) {
         constexpr bool SPECIAL = decltype(special_c)::value, MASKED = decltype(masked_c)::value;
         const int j = vis.tile(k), buf = k & 1;
@@ -294,14 +299,21 @@ __global__ __launch_bounds__(256, 3) void attn_mx4_kernel(const Mx4Params p) {
         f32x16 st[2];
         uint32_t pk[8];
         __builtin_amdgcn_s_setprio(1);
-        if (FOLD && !SPECIAL) qk_tile4(Ksm + buf * Tile4::KBYTES, kscale[buf], qf, qs, st, ql, hh, &start);
+        if (FOLD && !SPECIAL && !NOEXP) qk_tile4(Ksm + buf * Tile4::KBYTES, kscale[buf], qf, qs, st, ql, hh, &start);
         else qk_tile4(Ksm + buf * Tile4::KBYTES, kscale[buf], qf, qs, st, ql, hh);
         __builtin_amdgcn_s_setprio(0);
         const bool needs_mask = (p.causal && j * BN + BN - 1 > row0) || (j + 1) * BN > N;
-        if (FOLD && !SPECIAL) softmax_tile8_folded<MASKED, P_BF8>(st, pk, lsum, j * BN, needs_mask ? limit : 0x3fffffff, hh);
+        if (NOEXP && !SPECIAL) codes_tile8<MASKED>(st, pk, j * BN, needs_mask ? limit : 0x3fffffff, hh, code0);
+        else if (NOEXP) special_tile8_noexp<MASKED>(st, pk, ot, lt, m2, p.headroom, j * BN, needs_mask ? limit : 0x3fffffff, hh);
+        else if (FOLD && !SPECIAL) softmax_tile8_folded<MASKED, P_BF8>(st, pk, lsum, j * BN, needs_mask ? limit : 0x3fffffff, hh);
         else softmax_tile8<SPECIAL, MASKED, P_BF8>(st, pk, ot, m2, lsum, p.c, p.headroom, j * BN, needs_mask ? limit : 0x3fffffff, hh);
         __builtin_amdgcn_s_setprio(1);
         pv_tile8<P_BF8>(Vsm + buf * Tile8::VBYTES, pk, ot, lane, hh);
+        if (NOEXP) {  // row sums of the rounded weights: a block of E2M1 ones times P (E5M2)
+            const i32x8 ones = {0x22222222, 0x22222222, 0x22222222, 0x22222222, 0, 0, 0, 0};
+            const i32x8 pf = {(int)pk[0], (int)pk[1], (int)pk[2], (int)pk[3], (int)pk[4], (int)pk[5], (int)pk[6], (int)pk[7]};
+            lt = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ones, pf, lt, 4, 1, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+        }
         __builtin_amdgcn_s_setprio(0);
         wait_vm0_and_sync();
     };
@@ -321,12 +333,14 @@ __global__ __launch_bounds__(256, 3) void attn_mx4_kernel(const Mx4Params p) {
     for (; k < n_lead; ++k) visit(k, true_type{}, true_type{});
     if (FOLD) {
         const float v = -(m2 + p.headroom);
+        if (NOEXP) code0 = kCodeOffset + kCodesPerBinade * v;
 #pragma unroll
         for (int r = 0; r < 16; ++r) start[r] = v;
     }
     for (; k < k_fast_end; ++k) visit(k, std::integral_constant<bool, TAIL_SPECIAL>{}, false_type{});
     for (; k < vis.total; ++k) visit(k, std::integral_constant<bool, TAIL_SPECIAL>{}, true_type{});
-    const float l = xhalf_sum(lsum);
+    // (NOEXP: every register of lt holds the whole row sum, with the same 2^15 as the numerator)
+    const float l = NOEXP ? lt[0] * 0x1p-15f : xhalf_sum(lsum);
     const float inv = l > 0.f ? p.descale_v * (P_BF8 ? 0x1p-15f : 0x1p-8f) / l : 0.f;
     if (qrow < N) {
         uint16_t* Og = p.O + ((size_t)(b * p.Hq + h) * N + qrow) * D;

@@ -494,10 +494,14 @@ int vfa_mxfp4_quantize(const void* X, void* X4, void* XS, long long n, float pre
     return hipGetLastError() == hipSuccess ? VFA_OK : VFA_ERR_HIP;
 }
 
-int vfa_mxfp4_attn_fwd(int frozen, const void* Q4, const void* QS, const void* K4, const void* KS, const void* Vt8, void* O,
-                       float* LSE, int B, int Hq, int Hkv, int N, int d, int block_m, int block_n, int causal, int n_sink,
-                       int n_local, int use_minit, float softmax_scale, float descale_v, void* workspace,
-                       size_t workspace_bytes, void* stream) {
+}  // extern "C"
+
+namespace {
+
+int mx4_common(int frozen, bool noexp, const void* Q4, const void* QS, const void* K4, const void* KS, const void* Vt8, void* O,
+               float* LSE, int B, int Hq, int Hkv, int N, int d, int block_m, int block_n, int causal, int n_sink,
+               int n_local, int use_minit, float softmax_scale, float descale_v, void* workspace,
+               size_t workspace_bytes, void* stream) {
     if (B < 0 || N < 0 || Hq <= 0 || Hkv <= 0 || d <= 0 || block_m <= 0 || block_n <= 0) return VFA_ERR_INVALID_ARG;
     if (Hq % Hkv != 0 || (frozen != 0 && frozen != 1)) return VFA_ERR_INVALID_ARG;
     if (!(descale_v > 0.f) || !isfinite(descale_v) || !isfinite(softmax_scale)) return VFA_ERR_INVALID_ARG;
@@ -520,6 +524,10 @@ int vfa_mxfp4_attn_fwd(int frozen, const void* Q4, const void* QS, const void* K
     hipStream_t s = (hipStream_t)stream;
     uint8_t* const repr = (uint8_t*)workspace;
     uint8_t* const repr_s = repr ? repr + (size_t)B * Hkv * Tc * 128 : nullptr;  // (a multiple of 128: dword aligned)
+    {
+        const float sc = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)d);
+        if (noexp && !(fabsf(sc * kLog2e - 1.f) <= 0x1p-18f)) return VFA_ERR_INVALID_ARG;  // (before anything is launched)
+    }
     (void)hipGetLastError();
     if (minit && use_minit == 1) {
         mx4_kblock_summary_kernel<<<dim3((unsigned)Tc, (unsigned)(B * Hkv)), 256, 0, s>>>((const uint8_t*)K4, (const uint8_t*)KS,
@@ -539,12 +547,33 @@ int vfa_mxfp4_attn_fwd(int frozen, const void* Q4, const void* QS, const void* K
     // Alg. 1 with the scores already in log2 units (the caller multiplied Q by scale * log2(e) before quantising
     // and passes softmax_scale = ln 2): nothing is left to multiply, and the frozen max becomes the accumulators' start
     const bool fold = frozen && fabsf(p.c - 1.f) <= 0x1p-18f;
-    if (fold) p.c = 1.f;
+    if (fold) p.c = noexp ? 0.25f : 1.f;  // (without exponentials the scores come out times 4)
     const dim3 grid((unsigned)(B * Hq * Tr));
-    if (fold) attn_mx4_kernel<MODE_VFA, true><<<grid, 256, 0, s>>>(p);
+    if (noexp) attn_mx4_kernel<MODE_VFA, true, true><<<grid, 256, 0, s>>>(p);
+    else if (fold) attn_mx4_kernel<MODE_VFA, true><<<grid, 256, 0, s>>>(p);
     else if (frozen) attn_mx4_kernel<MODE_VFA, false><<<grid, 256, 0, s>>>(p);
     else attn_mx4_kernel<MODE_FA, false><<<grid, 256, 0, s>>>(p);
     return hipGetLastError() == hipSuccess ? VFA_OK : VFA_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int vfa_mxfp4_attn_fwd(int frozen, const void* Q4, const void* QS, const void* K4, const void* KS, const void* Vt8, void* O,
+                       float* LSE, int B, int Hq, int Hkv, int N, int d, int block_m, int block_n, int causal, int n_sink,
+                       int n_local, int use_minit, float softmax_scale, float descale_v, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+    return mx4_common(frozen, false, Q4, QS, K4, KS, Vt8, O, LSE, B, Hq, Hkv, N, d, block_m, block_n, causal, n_sink, n_local,
+                      use_minit, softmax_scale, descale_v, workspace, workspace_bytes, stream);
+}
+
+int vfa_mxfp4_attn_noexp_fwd(const void* Q4, const void* QS, const void* K4, const void* KS, const void* Vt8, void* O,
+                             float* LSE, int B, int Hq, int Hkv, int N, int d, int block_m, int block_n, int causal,
+                             int n_sink, int n_local, int use_minit, float softmax_scale, float descale_v, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+    return mx4_common(1, true, Q4, QS, K4, KS, Vt8, O, LSE, B, Hq, Hkv, N, d, block_m, block_n, causal, n_sink, n_local,
+                      use_minit, softmax_scale, descale_v, workspace, workspace_bytes, stream);
 }
 
 const char* vfa_strerror(int code) {

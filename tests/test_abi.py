@@ -137,6 +137,11 @@ def test_bad_arguments_are_rejected_before_launch(pkg):
     assert m4(0, p, ctypes.c_void_p(0x1002), p, p, p, p, none, *f8shape, 1, 1, 1, 0.0, 1.0, p, 1 << 20, none) == -1
     assert m4(0, p, p, p, p, p, p, none, 1, 4, 2, 256, 64, 128, 64, 1, 1, 1, 1, 0.0, 1.0, p, 1 << 20, none) == -2   # d = 64
     assert m4(0, p, p, p, p, p, p, none, 0, 4, 2, 256, 128, 128, 64, 1, 1, 1, 1, 0.0, 1.0, none, 0, none) == 0
+    mn = lambda *a: L.vfa_mxfp4_attn_noexp_fwd(*a)
+    ln2 = 0.6931471805599453
+    assert mn(p, p, p, p, p, p, none, *f8shape, 1, 1, 1, 0.0, 1.0, p, 1 << 20, none) == -1             # scale 2^-3.5: scores not in log2 units
+    assert mn(p, p, p, p, p, p, none, *f8shape, 1, 1, 1, ln2, 1.0, none, 0, none) == -1                 # workspace missing
+    assert mn(p, p, p, p, p, p, none, 0, 4, 2, 256, 128, 128, 64, 1, 1, 1, 1, ln2, 1.0, none, 0, none) == 0
     assert L.vfa_mxfp4_quantize(p, p, p, 48, 1.0, none) == -1                                         # not a multiple of 32
     assert L.vfa_mxfp4_quantize(p, p, p, 64, 0.0, none) == -1
     assert L.vfa_mxfp4_quantize(p, none, p, 64, 1.0, none) == -1

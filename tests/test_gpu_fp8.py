@@ -172,6 +172,25 @@ def test_fp8_frozen_max_far_too_low_is_capped_not_nan(vfa, oracle):
     assert np.abs(o).max() <= float(np.abs(pr["Vd"]).max()) * 1.01
 
 
+def test_fp8_noexp_full_size_sampled_blocks(vfa, oracle):
+    """cfg3 in the launch configuration bench.py times, checked on a sample of query blocks."""
+    import torch
+    w = wl.CONFIGS["cfg3"]
+    pr = quantised_problem(vfa, oracle, w, fold=True)
+    blocks = wl.sample_blocks(w, 6)
+    Oe, Le, Me = oracle.exact(pr["Qd"], pr["Kd"], pr["Vd"], w.block_m, w.causal, blocks)
+    vmax = float(np.abs(pr["Vd"]).max())
+    O, L = vfa.fp8_attn_fwd(pr["Q8"], pr["K8"], pr["Vt8"], noexp=True, n_sink=w.n_sink, n_local=w.n_local, descale_q=pr["sq"],
+                            descale_k=pr["sk"], descale_v=pr["sv"], block_m=w.block_m, block_n=w.block_n, causal=w.causal)
+    torch.cuda.synchronize()
+    got_O, got_L = gather_blocks(O, blocks, w.block_m, w.N), gather_blocks(L, blocks, w.block_m, w.N)
+    err = np.abs(got_O - Oe)
+    lerr = np.abs(got_L - Le).max()
+    print("cfg3 fp8 no exp max_abs %.4f mean_abs %.5f lse %.3f" % (err.max(), err.mean(), lerr), flush=True)
+    assert not np.isnan(got_O).any()
+    assert err.max() <= vmax / 8 * 1.05 + 2e-2 and err.mean() <= vmax / 8 / 8 and lerr <= 0.12
+
+
 def test_fp8_full_size_sampled_blocks(vfa, oracle):
     """cfg3 in the launch configuration bench.py times, checked on a sample of query blocks."""
     import torch
