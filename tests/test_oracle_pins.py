@@ -118,6 +118,45 @@ def test_sabsmax_properties(oracle):
     assert np.array_equal(oracle.sabsmax(K[:, :, :64], 16), oracle.sabsmax(K2, 16))
 
 
+def test_alternative_block_representations_hand_worked(oracle):
+    """The ablated summaries (Experiments, ablation of the k_repr construction) on the block
+    [[1,-3],[-2,2]], worked by hand: per-dimension max [1, 2], mean [-0.5, -0.5], magnitude
+    without sign [2, 3]; the method's signed extreme is [-2, -3]."""
+    blk = np.array([[1, -3], [-2, 2]], np.float32)[None, None]
+    for mode, want in ((0, [-2.0, -3.0]), (1, [1.0, 2.0]), (2, [-0.5, -0.5]), (3, [2.0, 3.0])):
+        assert np.array_equal(oracle.sabsmax(blk, 2, mode)[0, 0, 0], want), mode
+    # an all-negative column: the maximum is the element closest to zero, not the extreme
+    neg = np.array([[-1, 4], [-5, -4], [-3, 0]], np.float32)[None, None]
+    assert np.array_equal(oracle.sabsmax(neg, 3, 1)[0, 0, 0], [-1.0, 4.0])
+    assert np.array_equal(oracle.sabsmax(neg, 3, 3)[0, 0, 0], [5.0, 4.0])
+    assert np.array_equal(oracle.sabsmax(neg, 3, 2)[0, 0, 0], [-3.0, 0.0])
+
+
+@pytest.mark.parametrize("bn", [8, 16, 32])
+def test_alternative_block_representations_match_library_reductions(oracle, bn):
+    """Modes 1, 2, 3 over key blocks against numpy's max / mean / abs-max, block by block, with a
+    ragged last block (70 keys) reduced over its valid rows only."""
+    N = 70
+    K = rnd(17, 2, 3, N, 5)
+    K[0, 1, 3:9] -= 6.0           # a block whose entries are all negative in every dimension
+    lib = {1: lambda x: x.max(2), 2: lambda x: x.mean(2), 3: lambda x: np.abs(x).max(2)}
+    Tc = -(-N // bn)
+    for mode, f in lib.items():
+        R = oracle.sabsmax(K, bn, mode)
+        assert R.shape == (2, 3, Tc, 5)
+        for j in range(Tc):
+            blk = K[:, :, j * bn: min(N, (j + 1) * bn)].astype(np.float64)
+            want = f(blk)
+            if mode == 2:
+                assert np.abs(R[:, :, j] - want).max() < 1e-15, (mode, j)
+            else:
+                assert np.array_equal(R[:, :, j], want), (mode, j)
+    # orderings that separate the four summaries from one another on generic data
+    R0, R1, R2, R3 = (oracle.sabsmax(K, bn, m) for m in range(4))
+    assert np.all(R1 <= R3) and np.all(np.abs(R0) == R3) and np.all(R2 <= R1)
+    assert (R1 < R3).any() and (R0 != R1).any()
+
+
 # ------------------------------------------------------------------ visit order
 def test_visit_order_golden(oracle):
     for line in open(os.path.join(GOLDEN, "visit_order.txt")):
