@@ -1,10 +1,13 @@
 /*
  * vfa.h -- C ABI of libvfa.so: the VFA / VSA attention forward path for AMD MI355X (gfx950).
  *
- * Every pointer is a DEVICE pointer owned by the caller.  The library allocates nothing,
- * frees nothing and keeps no state between calls.  Calls are asynchronous: they enqueue
- * kernels on `stream` (a hipStream_t passed as void*, NULL = the default stream) and return;
- * the caller keeps every buffer alive until the stream has passed the call.
+ * Every pointer is a DEVICE pointer owned by the caller.  The library allocates nothing and
+ * frees nothing.  Between calls it remembers only per-device facts that do not depend on the
+ * arguments (the CU count, that a kernel's LDS limit has been raised, the address of its one
+ * device array), held in atomics: calls may come from several host threads and for several
+ * devices (the current device of the calling thread is used).  Calls are asynchronous: they
+ * enqueue kernels on `stream` (a hipStream_t passed as void*, NULL = the default stream) and
+ * return; the caller keeps every buffer alive until the stream has passed the call.
  *
  * Tensor layouts (row-major, last index contiguous, 16-byte aligned base pointers):
  *   Q, O   [B, Hq,  N, d]  bf16
@@ -23,9 +26,9 @@
  * The functions never throw, abort or print.  Same inputs give bit-identical outputs.
  *
  * Calls may be recorded into a HIP graph (they only enqueue kernels; nothing is allocated, copied
- * or cleared).  One exception: the first launch of an attention kernel that needs more than 64 KiB
- * of LDS (d = 128 with block_m = 128) sets that function attribute, so make one ordinary call per
- * entry point and process before capturing.
+ * or cleared).  One exception: the first launch, on each device, of an attention kernel that needs
+ * more than 64 KiB of LDS (d = 128 with block_m = 128) sets that function attribute, so make one
+ * ordinary call per entry point, device and process before capturing.
  */
 #ifndef VFA_H_
 #define VFA_H_
@@ -45,7 +48,7 @@ extern "C" {
  * to 256 bytes).  Returns 0 for invalid arguments. */
 size_t vfa_workspace_bytes(int B, int Hkv, int N, int d, int block_n);
 
-/* Key-block summary pre-pass (Alg. 1, "precompute key-block representations"; Methods, Step 1):
+/* Key-block summary pre-pass (Alg. 1, its first loop; Methods, Step 1):
  * Krepr[b, h, j, t] = the element of K[b, h, j*block_n : (j+1)*block_n, t] with the largest
  * absolute value, sign kept; when +a and -a tie, +a.  The result is an element of K, so bf16
  * is exact.  vfa_attn_fwd / vsa_attn_fwd run this themselves; it is exported for callers that
@@ -53,8 +56,8 @@ size_t vfa_workspace_bytes(int B, int Hkv, int N, int d, int block_n);
 int vfa_kblock_summary(const void* K, void* Krepr, int B, int Hkv, int N, int d, int block_n,
                        void* stream);
 
-/* The same pre-pass with the block representations of the k_repr ablation (Experiments, "Ablating
- * the k_repr construction"): repr_mode 0 = sabsmax (as above), 1 = per-dimension maximum,
+/* The same pre-pass with the block representations of the k_repr ablation (Experiments, the
+ * ablation of how k_repr is built): repr_mode 0 = sabsmax (as above), 1 = per-dimension maximum,
  * 2 = per-dimension mean (fp32 sum, rounded to bf16), 3 = per-dimension largest magnitude without
  * its sign.  VFA_ERR_INVALID_ARG for any other mode. */
 int vfa_kblock_summary_mode(const void* K, void* Krepr, int B, int Hkv, int N, int d, int block_n,
@@ -66,9 +69,9 @@ int fa_baseline_fwd(const void* Q, const void* K, const void* V, void* O, float*
                     int Hq, int Hkv, int N, int d, int block_m, int block_n, int causal,
                     float softmax_scale, void* stream);
 
-/* Online softmax with conditional rescale: the second comparison kernel (related work on
- * FlashAttention-4, "conditionally eliding the output rescale"; appendix, variant Blasst_FA4,
- * its rescale-skip rule without the block skipping).  As fa_baseline_fwd, except that a query
+/* Online softmax with conditional rescale: the second comparison kernel (related work, the
+ * paragraph on FlashAttention-4; appendix, variant Blasst_FA4, its rescale-skip rule without the
+ * block skipping).  As fa_baseline_fwd, except that a query
  * row adopts the new running max only when it exceeds the old one by more than
  * rescale_tau * ln 2 (rescale_tau >= 0, finite, in factors of two; 8 is the usual choice);
  * otherwise the row keeps its old max, its scale factor is exactly 1, and when this holds for
@@ -117,8 +120,8 @@ int vsa_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LS
                  unsigned char* skip_mask, void* workspace, size_t workspace_bytes, void* stream);
 
 /* VFA / VSA with the switches of the ablation study and of the sparse-attention variants
- * (Experiments: "Ablating the k_repr construction", "Removing m-initialization", "Ablating the
- * reordered schedule", "Replacing row-wise approximation with block-wise approximation on Q";
+ * (Experiments, the four ablation paragraphs: construction of k_repr, no m-initialisation, no
+ * reordering, one summary per query block instead of row-wise approximate scores;
  * appendix: variants Blasst, Blasst_SWA, Blasst_Rowskip, Blasst_FA4).  As vfa_attn_fwd / vsa_attn_fwd,
  * plus:
  *   repr_mode  block representation used when use_minit == 1 (see vfa_kblock_summary_mode)
@@ -151,8 +154,8 @@ int vfa_variant_fwd(const void* Q, const void* K, const void* V, void* O, float*
                     float skip_threshold_nats, unsigned char* skip_mask, void* workspace,
                     size_t workspace_bytes, void* stream);
 
-/* Summaries of a growing key cache (Methods, Step 1: "for decoding with a growing KV-cache, this
- * precomputation can be performed incrementally for newly appended key blocks").  K is a cache
+/* Summaries of a growing key cache (Methods, Step 1: during decoding only newly appended key blocks
+ * need their summary computed).  K is a cache
  * [B, Hkv, n_cap, d] whose first n_new rows are valid, of which rows [n_old, n_new) are new;
  * Krepr is [B, Hkv, ceil(n_cap / block_n), d] (vfa_workspace_bytes(B, Hkv, n_cap, d, block_n)
  * bytes).  Recomputes exactly the summaries of the blocks that contain new rows (a partly filled

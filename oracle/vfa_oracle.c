@@ -13,8 +13,8 @@
  *                     the whole N x N matrix materialised (tiny inputs only).
  *   oracle_exact      the same definition, row by row in two passes (max, then
  *                     sum), for chosen query blocks of a large problem.
- *   oracle_sabsmax    Alg. 1 "precompute key-block representations" and the
- *                     sentence defining sabsmax in "Step 1".
+ *   oracle_sabsmax    Alg. 1, its first loop (one summary per key block), and the
+ *                     sentence defining sabsmax in Methods, Step 1.
  *   oracle_visit_list Alg. 1 main-loop order <1, i, 2, 3, ...> (Step 2),
  *                     generalised as stated below.
  *   oracle_blocks     Alg. 1 (VFA), Alg. 2 (VSA) and the FA column of Table 1

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <math.h>
+#include <atomic>
 
 #include "vfa.h"
 
@@ -36,17 +37,40 @@ int check_common(const void* Q, const void* K, const void* V, void* O, const flo
     return VFA_OK;
 }
 
+// Host-side caches.  Everything the library remembers between calls is a per-device fact that any thread would
+// compute to the same value (a CU count, "this kernel's LDS limit has been raised", the address of the device
+// array below), held in atomics: two threads that race on a first call both do the lookup and store the same thing.
+constexpr int kMaxDevices = 64;
+
+int current_device() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return -1;
+    return dev;
+}
+
 // number of compute units of the current device (0 if the query fails), looked up once per device
 int cu_count() {
-    static int cached[64];
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
-    if (cached[dev] == 0) {
-        int n = 0;
+    static std::atomic<int> cached[kMaxDevices];
+    const int dev = current_device();
+    if (dev < 0) return 0;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = -1;
-        cached[dev] = n;
+        cached[dev].store(n, std::memory_order_relaxed);
     }
-    return cached[dev] > 0 ? cached[dev] : 0;
+    return n > 0 ? n : 0;
+}
+
+// opt a kernel in to more than 64 KiB of LDS, once per kernel and device (idempotent, so a race only repeats it)
+template <typename KernelT>
+bool raise_lds_limit(KernelT kernel, int bytes, std::atomic<unsigned char>* done) {
+    const int dev = current_device();
+    if (dev < 0) return false;
+    if (done[dev].load(std::memory_order_acquire)) return true;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess)
+        return false;
+    done[dev].store(1, std::memory_order_release);
+    return true;
 }
 
 template <int MODE>
@@ -60,13 +84,8 @@ int launch_fwd(const Params& p, int d, int block_m, hipStream_t s) {
     if (d == 128 && block_m == 128 && !p.order_asc && !p.all_special && !p.rowskip && !p.Qrepr &&
         !(MODE == MODE_VSA && p.tau2 >= 0.f) &&
         (head_pairs || MODE != MODE_VSA || (p.causal && p.n_local <= 1))) {
-        static bool attr_set = false;  // opt in to more than 64 KB of LDS once per instantiation
-        if (!attr_set) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_pp_kernel<MODE>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, PP_LDS_BYTES) != hipSuccess)
-                return VFA_ERR_HIP;
-            attr_set = true;
-        }
+        static std::atomic<unsigned char> lds_raised[kMaxDevices];  // one set of flags per instantiation
+        if (!raise_lds_limit(&attn_fwd_pp_kernel<MODE>, PP_LDS_BYTES, lds_raised)) return VFA_ERR_HIP;
         Params q = p;
         q.pair_blocks = head_pairs ? 0 : 1;
         unsigned n_wg = (unsigned)(head_pairs ? p.B * (p.Hq / 2) * p.Tr : p.B * p.Hq * ((p.Tr + 1) / 2));

@@ -71,3 +71,42 @@ def test_full_size_sampled_blocks(oracle, name, n_random):
     sp = (ref["mask"] == 1).sum() / max(1, (ref["mask"] != 2).sum())
     full_sp = float((Mh == 1).sum()) / float((Mh != 2).sum())
     print(name, "vsa", stats, "sampled sparsity %.3f, whole-problem sparsity %.3f, near-threshold tiles %d" % (sp, full_sp, near.sum()), flush=True)
+
+
+# VSA where tiles really are skipped, in the launch configuration of the headline workload (head pairs,
+# persistent workgroups): at cfg3's own threshold of 8 nats nothing is skipped, so the cases above exercise only
+# the "keep" side there.  4 nats skips roughly a fifth of the visited tiles, 2 nats most of them.
+VSA_CASES = [("cfg3", 4.0, 12, 0.05, 0.6), ("cfg3", 2.0, 8, 0.5, 0.99)]
+
+
+@pytest.mark.parametrize("name,thr,n_random,sp_lo,sp_hi", VSA_CASES, ids=[f"{c[0]}-{c[1]}nats" for c in VSA_CASES])
+def test_full_size_vsa_with_skipping(oracle, name, thr, n_random, sp_lo, sp_hi):
+    import torch
+    import paper_2604_12798_amd as vfa
+    vfa.lib()
+    w = wl.CONFIGS[name]
+    print(f"{name} thr {thr}: generating", flush=True)
+    t = wl.generate(w)
+    Q, K, V = gpu_inputs(t)
+    Qh, Kh, Vh = host_f32(t)
+    blocks = wl.sample_blocks(w, n_random)
+    vkw = dict(n_sink=w.n_sink, n_local=w.n_local, block_m=w.block_m, block_n=w.block_n, causal=w.causal)
+    print(f"{name} thr {thr}: oracle Alg. 2 on {len(blocks)} blocks", flush=True)
+    ref = oracle.blocks(Qh, Kh, Vh, w.block_m, w.block_n, w.causal, blocks, n_sink=w.n_sink, n_local=w.n_local,
+                        vsa=True, skip_threshold_nats=thr)
+    O, L, M = vfa.vsa_attn_fwd(Q, K, V, skip_threshold_nats=thr, **vkw)
+    torch.cuda.synchronize()
+    Mh = M.cpu().numpy()
+    got = np.stack([Mh[b, h, i] for b, h, i in blocks])
+    near = np.abs(ref["margin"]) < MASK_GUARD_NATS
+    assert near.sum() <= 0.001 * near.size + 2, "too many tiles sit on the threshold"
+    assert np.array_equal(got[~near], ref["mask"][~near]), int((got[~near] != ref["mask"][~near]).sum())
+    clean = ~near.any(axis=1)
+    stats = check_o_lse(O, L, ref["O"][clean], ref["LSE"][clean], blocks[clean], w.block_m, w.N, "vsa_attn_fwd vs oracle")
+    full_sp = float((Mh == 1).sum()) / float((Mh != 2).sum())
+    print(name, f"vsa at {thr} nats", stats, "whole-problem sparsity %.3f, near-threshold tiles %d" % (full_sp, near.sum()), flush=True)
+    assert sp_lo <= full_sp <= sp_hi, "the case no longer skips what it is meant to skip"
+    # the same call twice: bit-identical outputs and mask (deterministic vote, no atomics)
+    O2, L2, M2 = vfa.vsa_attn_fwd(Q, K, V, skip_threshold_nats=thr, **vkw)
+    torch.cuda.synchronize()
+    assert torch.equal(M, M2) and torch.equal(O, O2) and torch.equal(L, L2)
