@@ -43,6 +43,7 @@ extern "C" {
 #define VFA_ERR_INVALID_ARG (-1) /* null/misaligned pointer, negative size, Hq % Hkv != 0, bad flag combination, workspace too small */
 #define VFA_ERR_UNSUPPORTED (-2) /* d or block sizes outside the compiled set, sizes beyond 32-bit grid limits */
 #define VFA_ERR_HIP (-3)         /* the HIP runtime reported a launch error */
+#define VFA_ERR_TOO_LARGE (-4)   /* vfa_decode_noalloc_fwd only: the partial sums do not fit the library's fixed device array */
 
 /* Bytes of `workspace` that vfa_attn_fwd / vsa_attn_fwd need (the Krepr tensor, rounded up
  * to 256 bytes).  Returns 0 for invalid arguments. */
@@ -185,6 +186,26 @@ int vfa_decode_fwd(const void* Q, const void* K, const void* V, const void* Krep
                    float* LSE, int B, int Hq, int Hkv, int n_cap, int n_keys, int d, int block_n,
                    int n_sink, int n_local, int use_minit, int n_splits, float softmax_scale,
                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* vfa_decode_fwd for callers that cannot allocate and have no workspace to hand over: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, layouts, kernels
+ * and results (bit for bit) as vfa_decode_fwd, minus the workspace: the partial sums of the key ranges live
+ * in one fixed array of VFA_DECODE_NOALLOC_MAX_BYTES bytes of device memory that is part of the library's
+ * code object (each device the library is used on holds one copy until the process ends).  The call
+ * allocates nothing, frees nothing, clears nothing (every slot that is read is written earlier in the same
+ * call) and enqueues the same three kernels on `stream`.
+ * Limit: B * Hq * n_splits * (2 + d) * 4 bytes <= VFA_DECODE_NOALLOC_MAX_BYTES (4 MiB: 8065 (head, range)
+ * rows at d = 128, e.g. B * Hq = 504 with 16 ranges), else VFA_ERR_TOO_LARGE and nothing is launched.
+ * The first call on a device looks the array's address up (hipGetSymbolAddress; VFA_ERR_HIP if that fails):
+ * make it outside graph capture.
+ * All calls on one device share the array: two calls that may run at the same time on one device (different
+ * streams, or replays of two graphs) race on it and must be serialised by the caller; calls on one stream are
+ * ordered and safe.  The array keeps the last call's contents, which no later call reads. */
+#define VFA_DECODE_NOALLOC_MAX_BYTES (4u << 20)
+int vfa_decode_noalloc_fwd(const void* Q, const void* K, const void* V, const void* Krepr, void* O,
+                           float* LSE, int B, int Hq, int Hkv, int n_cap, int n_keys, int d,
+                           int block_n, int n_sink, int n_local, int use_minit, int n_splits,
+                           float softmax_scale, void* stream);
 
 /* The two decode calls for a batch whose sequences have different lengths.  old_lens / new_lens /
  * seq_lens are DEVICE arrays of B ints (4-byte aligned), read by the kernels (the host never looks at

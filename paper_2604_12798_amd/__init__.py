@@ -15,7 +15,7 @@ _lib = None
 
 EXPORTS = ("vfa_workspace_bytes", "vfa_kblock_summary", "vfa_kblock_summary_mode", "fa_baseline_fwd",
            "fa_lazy_rescale_fwd", "fa_lazy_rescale_softexp_fwd", "vfa_attn_fwd", "vsa_attn_fwd", "vfa_variant_fwd", "vfa_kblock_summary_append",
-           "vfa_decode_workspace_bytes", "vfa_decode_fwd", "vfa_kblock_summary_append_varlen", "vfa_decode_varlen_fwd", "vfa_fp8_quantize", "vfa_fp8_v_bytes", "vfa_fp8_pack_v",
+           "vfa_decode_workspace_bytes", "vfa_decode_fwd", "vfa_decode_noalloc_fwd", "vfa_kblock_summary_append_varlen", "vfa_decode_varlen_fwd", "vfa_fp8_quantize", "vfa_fp8_v_bytes", "vfa_fp8_pack_v",
            "vfa_fp8_attn_fwd", "vfa_fp8_attn_noexp_fwd", "vfa_mxfp4_quantize", "vfa_mxfp4_workspace_bytes", "vfa_mxfp4_attn_fwd", "vfa_mxfp4_attn_noexp_fwd", "vfa_strerror")
 
 
@@ -47,6 +47,8 @@ def lib() -> ctypes.CDLL:
         L.vfa_decode_workspace_bytes.argtypes = [i, i, i, i]
         L.vfa_decode_fwd.restype = i
         L.vfa_decode_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, i, i, f, vp, sz, vp]
+        L.vfa_decode_noalloc_fwd.restype = i
+        L.vfa_decode_noalloc_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, i, i, f, vp]
         L.vfa_kblock_summary_append_varlen.restype = i
         L.vfa_kblock_summary_append_varlen.argtypes = [vp, vp, i, i, i, vp, vp, i, i, vp]
         L.vfa_decode_varlen_fwd.restype = i
@@ -302,6 +304,23 @@ def decode_fwd(q, K, V, n_keys: int, *, krepr=None, block_n=64, n_sink=1, n_loca
     if rc != 0:
         raise VfaError(rc, "vfa_decode_fwd")
     return O, L
+
+
+DECODE_NOALLOC_MAX_BYTES = 4 << 20   # VFA_DECODE_NOALLOC_MAX_BYTES of vfa.h
+
+
+def decode_noalloc_fwd(q, K, V, n_keys: int, out, lse=None, *, krepr=None, block_n=64, n_sink=1, n_local=1, use_minit=True,
+                       n_splits=8, softmax_scale=0.0, stream=None):
+    """vfa_decode_noalloc_fwd: as decode_fwd, but neither the library nor this wrapper allocates: the caller passes
+    the output tensors (lse may be None) and the partial sums live in the library's fixed device array."""
+    B, Hq, d = q.shape
+    Hkv, n_cap = K.shape[1], K.shape[2]
+    rc = lib().vfa_decode_noalloc_fwd(_ptr(q), _ptr(K), _ptr(V), _ptr(krepr), _ptr(out), _ptr(lse), B, Hq, Hkv, n_cap,
+                                      int(n_keys), d, block_n, int(n_sink), int(n_local), int(bool(use_minit)),
+                                      int(n_splits), float(softmax_scale), _stream(stream))
+    if rc != 0:
+        raise VfaError(rc, "vfa_decode_noalloc_fwd")
+    return out, lse
 
 
 def fp8_quantize(X, inv_scale: float, stream=None):

@@ -201,6 +201,32 @@ int decode_common(const void* Q, const void* K, const void* V, const void* Krepr
 
 }  // namespace
 
+// The one device array of the library: the partial sums of vfa_decode_noalloc_fwd's key ranges (what the
+// workspace argument carries in vfa_decode_fwd).  Every device the library is used on holds its own copy, at
+// its own address, until the process ends.  In host code the name below is only a handle for
+// hipGetSymbolAddress: the kernels receive the address that call returns, never the name.
+static __device__ __align__(256) unsigned char scratch[VFA_DECODE_NOALLOC_MAX_BYTES];
+
+namespace {
+
+// device address of `scratch` on the calling thread's current device; looked up on the first call per device
+void* scratch_address() {
+    static std::atomic<void*> addr[kMaxDevices];
+    const int dev = current_device();
+    if (dev < 0) return nullptr;
+    void* ptr = addr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        addr[dev].store(ptr, std::memory_order_release);
+    }
+    return ptr;
+}
+
+}  // namespace
+
 extern "C" {
 
 size_t vfa_workspace_bytes(int B, int Hkv, int N, int d, int block_n) {
@@ -304,6 +330,22 @@ int vfa_decode_fwd(const void* Q, const void* K, const void* V, const void* Krep
     if (n_keys < 1 || n_keys > n_cap) return VFA_ERR_INVALID_ARG;
     return decode_common(Q, K, V, Krepr, O, LSE, B, Hq, Hkv, n_cap, n_keys, nullptr, d, block_n, n_sink, n_local, use_minit,
                          n_splits, softmax_scale, workspace, workspace_bytes, stream);
+}
+
+int vfa_decode_noalloc_fwd(const void* Q, const void* K, const void* V, const void* Krepr, void* O, float* LSE, int B,
+                           int Hq, int Hkv, int n_cap, int n_keys, int d, int block_n, int n_sink, int n_local,
+                           int use_minit, int n_splits, float softmax_scale, void* stream) {
+    if (n_keys < 1 || n_keys > n_cap) return VFA_ERR_INVALID_ARG;
+    if (B < 0 || Hq <= 0 || d <= 0 || n_splits < 1) return VFA_ERR_INVALID_ARG;
+    if (B == 0) return VFA_OK;
+    // (rows * (2 + d) floats, in 64-bit arithmetic: the size check must not itself overflow)
+    if ((unsigned long long)B * (unsigned long long)Hq * (unsigned long long)n_splits * (2ull + (unsigned long long)d) * 4ull >
+        (unsigned long long)VFA_DECODE_NOALLOC_MAX_BYTES)
+        return VFA_ERR_TOO_LARGE;
+    void* const ws = scratch_address();
+    if (!ws) return VFA_ERR_HIP;
+    return decode_common(Q, K, V, Krepr, O, LSE, B, Hq, Hkv, n_cap, n_keys, nullptr, d, block_n, n_sink, n_local, use_minit,
+                         n_splits, softmax_scale, ws, VFA_DECODE_NOALLOC_MAX_BYTES, stream);
 }
 
 int vfa_decode_varlen_fwd(const void* Q, const void* K, const void* V, const void* Krepr, void* O, float* LSE, int B,
@@ -601,6 +643,7 @@ const char* vfa_strerror(int code) {
         case VFA_ERR_INVALID_ARG: return "invalid argument";
         case VFA_ERR_UNSUPPORTED: return "unsupported shape (d must be 64 or 128; blocks 64x64 or 128x64)";
         case VFA_ERR_HIP: return "HIP launch error";
+        case VFA_ERR_TOO_LARGE: return "problem needs more scratch than the library's fixed device array holds (use the entry point that takes a workspace)";
         default: return "unknown error code";
     }
 }
