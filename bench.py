@@ -11,9 +11,11 @@ skipped while the row max grows by less than 2^8) and vsa_attn_fwd, and reported
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import math
 import os
+import re
 import sys
 import time
 
@@ -25,9 +27,99 @@ sys.path.insert(0, ROOT)
 from paper_2604_12798_amd import workloads as wl  # noqa: E402
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
-# measured HBM bytes of one VFA attention launch: (FETCH_SIZE KiB * 1.954 + WRITE_SIZE KiB * 1.0) * 1024
-TRAFFIC_BYTES = {"cfg3": int((4.492e5 * 1.954 + 2.662e5) * 1024)}
 METRIC = "attn fwd TFLOP/s + % MFMA bf16 peak, VFA/VSA vs online-softmax baseline"
+
+
+def measured_traffic(name: str):
+    """HBM bytes of one attention launch as the rocprofv3 FETCH_SIZE / WRITE_SIZE runs measured them: read from the
+    committed profile summary of the workload (its line `traffic_bytes_per_launch: N`), null when there is none."""
+    path = os.path.join(ROOT, "profiles", f"attn_fwd_{name}.md")
+    try:
+        for line in open(path):
+            m = re.match(r"\s*traffic_bytes_per_launch\s*[:=]\s*([0-9]+)", line)
+            if m:
+                return int(m.group(1))
+    except OSError:
+        pass
+    return None
+
+
+def time_sustained(fn, seconds=1.0, chunk=20):
+    """ms per call over at least `seconds` of back-to-back launches (no host sync inside a chunk's queue)."""
+    import torch
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n, t0 = 0, time.perf_counter()
+    a.record()
+    while True:
+        for _ in range(chunk):
+            fn()
+        n += chunk
+        b.record()
+        b.synchronize()
+        if time.perf_counter() - t0 >= seconds:
+            break
+    return a.elapsed_time(b) / n, n
+
+
+def mfma_ceiling(torch, dev, seed):
+    """The MFMA-only probe (bench_mfma_probe.hip, a library of its own): bf16 32x32x16 MFMAs on register operands,
+    two waves per SIMD as in the attention kernel, once on normally distributed operands and once on zeros."""
+    path = os.path.join(ROOT, "bench_mfma_probe.so")
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it with `python -m paper_2604_12798_amd.build`")
+    P = ctypes.CDLL(path)
+    P.mfma_probe_data_elems.restype = ctypes.c_size_t
+    P.mfma_probe_flop.restype = ctypes.c_double
+    P.mfma_probe_flop.argtypes = [ctypes.c_int, ctypes.c_int]
+    P.mfma_probe_launch.restype = ctypes.c_int
+    P.mfma_probe_launch.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    n = int(P.mfma_probe_data_elems())
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    blocks = torch.cuda.get_device_properties(0).multi_processor_count
+    iters = 6000      # 96000 MFMAs per wave: about 4 ms per launch
+    outb = torch.empty(blocks * 512, dtype=torch.float32, device=dev)
+    res = {}
+    for what, data in (("normal", torch.randn(n, generator=g).to(torch.bfloat16).to(dev)),
+                       ("zeros", torch.zeros(n, dtype=torch.bfloat16, device=dev))):
+        def run():
+            rc = P.mfma_probe_launch(ctypes.c_void_p(data.data_ptr()), ctypes.c_void_p(outb.data_ptr()), blocks, iters,
+                                     ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+            if rc != 0:
+                raise RuntimeError("mfma probe launch failed")
+        ms = time_region(run, 40, 10)
+        res[what] = float(P.mfma_probe_flop(blocks, iters)) / ms / 1e9
+    return res
+
+
+def frozen_tile_fraction(w: wl.Workload) -> float:
+    """Share of the visited (query block, key block) tiles that Alg. 1 handles with the frozen max, i.e. all but
+    the first n_sink blocks and the local blocks of each query block (counted, not measured)."""
+    visited = special = 0
+    for i in range(w.Tr):
+        r0, r1 = i * w.block_m, min(w.N, (i + 1) * w.block_m) - 1
+        a_lo, a_hi = r0 // w.block_n, r1 // w.block_n
+        j_hi = a_hi if w.causal else w.Tc - 1
+        sp = set(range(min(w.n_sink, j_hi + 1)))
+        if w.n_local > 0:
+            sp |= set(range(max(0, a_lo - (w.n_local - 1)), min(a_hi, j_hi) + 1))
+        visited += j_hi + 1
+        special += len(sp)
+    return 1.0 - special / visited
+
+
+def max_gap(w: wl.Workload, t: dict, n_random: int):
+    """max over sampled rows of (true row max - frozen max of Alg. 1), in nats, from the float64 oracle: how far above
+    the frozen max a score gets (<= 0 means the frozen max bounds every score of the row)."""
+    import oracle
+    Q, K, V = (wl.bf16_bits_to_f32(t[k]) for k in "QKV")
+    blocks = wl.sample_blocks(w, n_random)
+    ref = oracle.blocks(Q, K, V, w.block_m, w.block_n, w.causal, blocks, n_sink=w.n_sink, n_local=w.n_local)
+    _, _, Me = oracle.exact(Q, K, V, w.block_m, w.causal, blocks)
+    ok = ~np.isnan(Me)
+    gap = (Me - ref["m_final"])[ok]
+    return {"max_true_minus_frozen_max": float(gap.max()), "mean_true_minus_frozen_max": float(gap.mean()),
+            "rows": int(ok.sum()), "blocks": int(len(blocks))}
 
 
 def time_region(fn, steps, warmup):
@@ -99,6 +191,42 @@ def decode_step(args, torch, vfa):
             "peak_GB/s": 8000.0, "frac": nbytes / ms / 1e6 / 8000.0}
 
 
+def vsa_on_cfg5(args, torch, vfa):
+    """VSA on the workload it exists for (cfg5: N = 64K causal, graded attention mass, 8-nat threshold), against
+    Alg. 1 without skipping and the online-softmax baseline on the same inputs."""
+    w = wl.CONFIGS["cfg5"]
+    t = wl.generate(w, args.seed)
+    dev = torch.device("cuda:0")
+    Q, K, V = (torch.from_numpy(t[k].view(np.int16)).to(dev).view(torch.bfloat16) for k in "QKV")
+    O = torch.empty_like(Q)
+    L = torch.empty((w.B, w.Hq, w.N), dtype=torch.float32, device=dev)
+    ws = torch.empty(vfa.workspace_bytes(w.B, w.Hkv, w.N, w.d, w.block_n), dtype=torch.uint8, device=dev)
+    M = torch.empty((w.B, w.Hq, w.Tr, w.Tc), dtype=torch.uint8, device=dev)
+    kw = dict(block_m=w.block_m, block_n=w.block_n, causal=w.causal, out=O, lse=L)
+    vkw = dict(n_sink=w.n_sink, n_local=w.n_local, workspace=ws, **kw)
+    steps, warmup = max(10, args.steps // 2), max(3, args.warmup // 2)
+    ms_vfa = time_region(lambda: vfa.vfa_attn_fwd(Q, K, V, use_minit=1, **vkw), steps, warmup)
+    ms_fa = time_region(lambda: vfa.fa_baseline_fwd(Q, K, V, **kw), steps, warmup)
+    ms_vsa = time_region(lambda: vfa.vsa_attn_fwd(Q, K, V, use_minit=1, skip_threshold_nats=w.skip_threshold_nats,
+                                                   skip_mask=M, **vkw), steps, warmup)
+    torch.cuda.synchronize()
+    m = M.cpu().numpy()
+    sparsity = float((m == 1).sum()) / max(1, int((m != 2).sum()))
+    dense = w.dense_flop()
+    res = {"workload": f"cfg5: B={w.B} Hq={w.Hq} Hkv={w.Hkv} N={w.N} d={w.d} causal blocks {w.block_m}x{w.block_n}",
+           "skip_threshold_nats": w.skip_threshold_nats, "block_sparsity": sparsity, "steps": steps,
+           "vsa_ms": ms_vsa, "vfa_ms": ms_vfa, "fa_ms": ms_fa,
+           "dense_equivalent_tflops": dense / ms_vsa / 1e9,
+           "algorithmic_tflops": dense * (2.0 - sparsity) / 2.0 / ms_vsa / 1e9,
+           "pct_mfma_bf16_peak_algorithmic": 100.0 * dense * (2.0 - sparsity) / 2.0 / ms_vsa / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+           "vfa_tflops": dense / ms_vfa / 1e9, "fa_tflops": dense / ms_fa / 1e9,
+           "speedup_vs_vfa": ms_vfa / ms_vsa, "speedup_vs_fa": ms_fa / ms_vsa,
+           "frozen_tile_fraction": frozen_tile_fraction(w)}
+    if not args.no_cpu_baseline:
+        res["frozen_max_gap_nats"] = max_gap(w, t, 6)
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -108,7 +236,7 @@ def main():
     ap.add_argument("--seed", type=int, default=wl.DEFAULT_SEED)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=3500, help="random query blocks in the oracle timing sample")
-    ap.add_argument("--only", default="", help="comma list of fa,vfa,vsa,summary,decode,fp8,mxfp4 to time (default all; mxfp4 needs fp8)")
+    ap.add_argument("--only", default="", help="comma list of fa,vfa,vsa,summary,decode,fp8,mxfp4,ceiling,vsa_cfg5 to time (default all; mxfp4 needs fp8)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is a single-GPU kernel path; run it with --gpus 1 "
@@ -128,7 +256,7 @@ def main():
     M = torch.empty((w.B, w.Hq, w.Tr, w.Tc), dtype=torch.uint8, device=dev)
     kw = dict(block_m=w.block_m, block_n=w.block_n, causal=w.causal, out=O, lse=L)
     vkw = dict(n_sink=w.n_sink, n_local=w.n_local, workspace=ws, **kw)
-    only = set(filter(None, args.only.split(","))) or {"fa", "vfa", "vsa", "summary", "decode", "fp8", "mxfp4"}
+    only = set(filter(None, args.only.split(","))) or {"fa", "vfa", "vsa", "summary", "decode", "fp8", "mxfp4", "ceiling", "vsa_cfg5"}
 
     def run_vfa():
         vfa.vfa_attn_fwd(Q, K, V, use_minit=1, **vkw)
@@ -166,9 +294,22 @@ def main():
                   if (w.d == 128 and w.block_m == 128) else f"attn_fwd_kernel<{w.d},{w.block_m // 32},VFA>")
         out["roofline"] = {"bound": "mfma", "kernel": kernel, "achieved": dense / ms_k / 1e9,
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": dense / ms_k / 1e9 / MFMA_BF16_PEAK_TFLOPS,
-                           # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (profiles/attn_fwd_cfg3.md)
-                           "traffic": TRAFFIC_BYTES.get(w.name), "ms_per_launch": ms_k,
+                           # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (profiles/attn_fwd_<workload>.md)
+                           "traffic": measured_traffic(w.name), "ms_per_launch": ms_k,
                            "executed_tile_tflops": executed_tile_flop(w) / ms_k / 1e9}
+        # the same step looped for at least a second (the chip settles at the clock its power management grants)
+        ms_sus, n_sus = time_sustained(run_vfa, 1.0)
+        out["sustained"] = {"ms_per_step": ms_sus, "tflops": dense / ms_sus / 1e9, "launches": n_sus,
+                            "pct_mfma_bf16_peak": 100.0 * dense / ms_sus / 1e9 / MFMA_BF16_PEAK_TFLOPS}
+        out["frozen_tile_fraction"] = frozen_tile_fraction(w)
+    if "ceiling" in only:
+        # what the matrix cores alone deliver on this machine at the clock the chip grants them (operands in registers)
+        c = mfma_ceiling(torch, dev, args.seed)
+        out["mfma_ceiling"] = {"tflops_normal_operands": c["normal"], "tflops_zero_operands": c["zeros"],
+                               "kernel": "bench_mfma_probe.hip: v_mfma_f32_32x32x16_bf16 only, 2 waves per SIMD"}
+        if "vfa" in only:
+            out["pct_of_measured_ceiling"] = 100.0 * out["value"] / c["normal"]
+            out["roofline"]["frac_of_measured_ceiling"] = out["roofline"]["achieved"] / c["normal"]
     if "summary" in only:
         ms_s = time_region(run_summary, args.steps, args.warmup)
         kbytes = w.B * w.Hkv * w.N * w.d * 2 * (1 + 1.0 / w.block_n)
@@ -251,12 +392,16 @@ def main():
                                       "scale * log2(e) before quantising, frozen max into the accumulator start"}
             del Q4, QS, Q4f, QSf, K4, KS, ws4
         del Q8, K8, Vt8, ws8
+    if "vsa_cfg5" in only and w.name != "cfg5":
+        del Q, K, V, O, L, M, ws
+        out["vsa_cfg5"] = vsa_on_cfg5(args, torch, vfa)
     if "decode" in only:
         out["decode"] = decode_step(args, torch, vfa)
     out["paper_context"] = ("paper reports no measured kernel throughput; its analytic model gives ~2x for C8V32/C4V32/C4V16 "
                             "over C16V32 and 1.00x for VFA vs FA at C16V32 (the bf16 analogue) on its own accelerator")
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, t, args.cpu_sample)
+        out["frozen_max_gap_nats"] = max_gap(w, t, 24)   # oracle diagnostic on a small sample of query blocks
     print(json.dumps(out), flush=True)
 
 

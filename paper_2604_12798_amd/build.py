@@ -19,9 +19,11 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_lib(verbose: bool = False, extra: list[str] | None = None) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + (extra or []) + ["-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+PROBE_SRC = os.path.join(ROOT, "bench_mfma_probe.hip")   # bench.py's MFMA-only ceiling probe: a library of its own
+PROBE_LIB = os.path.join(ROOT, "bench_mfma_probe.so")
+
+
+def _run(cmd: list[str], verbose: bool) -> None:
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, capture_output=True, text=True)
@@ -30,8 +32,20 @@ def build_lib(verbose: bool = False, extra: list[str] | None = None) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err:
         print(err)
+
+
+def build_lib(verbose: bool = False, extra: list[str] | None = None) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    _run([hipcc] + HIPCC_FLAGS + (extra or []) + ["-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES], verbose)
     return LIB
+
+
+def build_probe(verbose: bool = False) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    _run([hipcc] + HIPCC_FLAGS + ["-o", PROBE_LIB, PROBE_SRC], verbose)
+    return PROBE_LIB
 
 
 if __name__ == "__main__":
     print(build_lib(verbose=True))
+    print(build_probe(verbose=True))
