@@ -111,10 +111,14 @@ int vfa_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LS
                  size_t workspace_bytes, void* stream);
 
 /* VSA forward (Alg. 2) = VFA plus the BLASST-style test on every visited tile: with
- * m~ = rowmax(S_ij) and m = the running max, the tile is skipped (no exp, no V load, no P.V)
- * iff m~ - max(m, m~) < -skip_threshold_nats for ALL rows of the query block
+ * m~ = rowmax(S_ij) and m = the running max, the tile is skipped iff
+ * m~ - max(m, m~) < -skip_threshold_nats for ALL rows of the query block
  * (skip_threshold_nats = -ln(lambda) > 0).  A skipped tile changes no state.  Rows whose
- * tiles were all skipped give O = 0, LSE = -inf. */
+ * tiles were all skipped give O = 0, LSE = -inf.
+ * What a skipped tile costs: its K tile, Q.K^T and the row max.  With d = 128 and block_m = 128
+ * (the ping-pong kernel) its V tile is never requested, no exponential is computed and no P.V
+ * runs: the decision is read one barrier after the vote, before any of them starts.  The other
+ * shapes (generic kernel) save the exponentials and the P.V but have fetched V by then. */
 int vsa_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int Hq,
                  int Hkv, int N, int d, int block_m, int block_n, int causal, int n_sink,
                  int n_local, int use_minit, float softmax_scale, float skip_threshold_nats,

@@ -1,4 +1,5 @@
-// Ping-pong bf16 attention kernel for d = 128, block_m = 128: the kernel the headline workloads run on.
+// Ping-pong bf16 attention kernel for d = 128, block_m = 128: the kernel the headline workloads run on
+// (Alg. 1 and the online-softmax baselines; Alg. 2 has a kernel of its own in attn_vsa.hpp).
 #pragma once
 #include "common.hpp"
 
@@ -22,7 +23,6 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
     using T = Tile<D>;
     constexpr int BM = 128, KK = D / 16, DB = D / 32, NWV = 8;
     extern __shared__ __attribute__((aligned(16))) uint8_t pp_smem[];
-    __shared__ int votes[2][2][4];
     uint8_t* const Ks = pp_smem;
     uint8_t* const Vs = pp_smem + PP_STAGES * T::BYTES;
 
@@ -104,21 +104,7 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
     float m2 = -INFINITY;
 
     Visit vis = make_visit<MODE>(p, a_lo, a_hi, j_hi);
-    if (MODE == MODE_VSA && pb) {
-        // Block pairs under Alg. 2 (causal, at most one local block per query block): the second block's
-        // local tiles come first (exact-max for group 1, invisible to group 0), then the first block's
-        // (exact-max for group 0, ordinary frozen tiles for group 1, whose max is final by then), so each
-        // group meets its own tiles in the order Alg. 2 gives them and takes the same skip decisions.
-        const int lo_b = (row0 + BM) / BN;  // first tile of the second block's diagonal
-        vis.n2b = vis.n2 > 0 ? max(0, vis.s2 + vis.n2 - max(vis.s2, lo_b)) : 0;
-    }
     const int nv = vis.total;
-    uint8_t* mrow = nullptr;
-    const int i_blk = pb ? 2 * i + grp : i;  // this group's query block
-    if (MODE == MODE_VSA && p.mask && i_blk < p.Tr) {
-        mrow = p.mask + ((size_t)(b * p.Hq + h) * p.Tr + i_blk) * p.Tc;
-        for (int j = j_hi_g + 1 + (tid & 255); j < p.Tc; j += 256) mrow[j] = 2;
-    }
 
     f32x16 ot[DB];
 #pragma unroll
@@ -213,16 +199,6 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
     };
     bf16x8 fa[4], fb[4];  // fragment double buffer of the matrix phase
 
-    auto vote = [&](int k) __attribute__((always_inline)) {  // VSA: this wave's say on "skip the tile of visit k"
-        const int j = vis.tile(k);
-        const float mx = tile_masked(j) ? tile_rowmax<true>(st, j * BN, limit, hh) : tile_rowmax<false>(st, 0, 0, hh);
-        const float mt2 = xhalf_max(mx) * p.c;
-        const bool row_keeps = (qrow < N) && (mt2 != -INFINITY) && !(mt2 < m2 - p.thr2);
-        const bool wave_keeps = __builtin_amdgcn_ballot_w64(row_keeps) != 0;
-        if (lane == 0) votes[k & 1][grp][w4] = wave_keeps ? 1 : 0;
-        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the vote is in LDS before this wave reaches the next barrier
-    };
-
     // Matrix phase of visit k in the steady state: P.V of visit k-1 (its chunk-0 fragments are already
     // in fa, fetched at the end of the vector phase), then Q.K^T of visit k.  Fragments for the next
     // four MFMAs are read from LDS while the current four issue.  Nothing else is on this path.
@@ -292,9 +268,8 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
         // vector phase on top.
         if (is_fa(MODE)) __builtin_amdgcn_s_setprio(2);
         fetch_ahead(k);
-        const bool keep = true;
-        pv_pending = keep;
-        if (keep) {
+        pv_pending = true;
+        {
             if (FAST)
                 softmax_tile<SPECIAL, false, DB, !FIRST, is_lazy(MODE), softexp_every(MODE)>(st, pk, ot, m2, lsum, p.c, j * BN,
                                                                                              limit, hh, p.tau2);
@@ -341,12 +316,12 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
     __syncthreads();
 
     // Visits split into: visit 0 (no P.V pending, nothing to rescale); the remaining sink/local visits
-    // of VFA / VSA (exact-max update); a run of unmasked visits that all take one path (frozen max for
-    // VFA, exact-max for FA; VSA does not use it because its tiles may be skipped); and the trailing
+    // of VFA (exact-max update); a run of unmasked visits that all take one path (frozen max for
+    // VFA, exact-max for FA); and the trailing
     // visits that may need masking (tiles on the diagonal or past the end of a ragged sequence).
     constexpr bool TAIL_SPECIAL = is_fa(MODE);
     const int n_lead = is_fa(MODE) ? 0 : vis.n_special;  // visits [0, n_lead) are sink/local
-    int k_fast_end = MODE == MODE_VSA ? n_lead : max(n_lead, 1);
+    int k_fast_end = max(n_lead, 1);
     {
         int j_masked = p.causal ? a_lo : p.Tc;  // first tile index that needs masking
         if (N % BN) j_masked = min(j_masked, p.Tc - 1);
@@ -412,145 +387,7 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_pp_kernel(const Params p) {
         }
         store_output<D>(p, ot, m2, lsum, b, h, qrow, hh);  // inside the per-group copy: nothing merges after it
     };
-    if constexpr (MODE == MODE_VSA) {
-        // VSA keeps the ping-pong schedule and its one barrier per tile by DEFERRING the block's decision: the
-        // matrix phase of visit k computes Q.K^T and casts this wave's vote; the vector phase runs the softmax
-        // of visit k speculatively into pk and three scalars (its row sum, and for an exact-max tile the new max
-        // and the rescale factor) without touching m, l or O; the NEXT matrix phase, one barrier later, reads the
-        // four votes, and only then commits (rescale, l, m, P.V) or drops the tile.  A skipped tile costs its
-        // Q.K^T, the row max and a wasted softmax on the vector ALU, which runs under the other group's MFMAs;
-        // it saves the P.V and, above all, needs no synchronisation of its own.
-        float lk = 0.f, alpha_k = 1.f, mnew_k = m2;  // what visit k - 1 left to commit
-        bool have_prev = false, prev_special = false;
-        int j_prev = 0;
-        int kb = kbase, vb = vbase;
-        // (fragments: four in flight, fragment i + 4 requested right behind the MFMA that consumed fragment i;
-        // the addresses are rebuilt per phase from a copy of the lane's base the compiler cannot see through)
-        auto pv_prev = [&](int k) __attribute__((always_inline)) {  // P.V of visit k
-            const uint8_t* vt = Vs + (k & 3) * T::BYTES;
-            asm volatile("" : "+v"(vb));
-            auto ldv1 = [&](int c, int db) __attribute__((always_inline)) {
-                const uint8_t* a = vt + (vb ^ (db << 6)) + 16 * c * T::ROWB;
-                const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(a));
-                const s16x4 v1 =
-                    __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(a + 8 * T::ROWB));
-                const u32x2 a0 = __builtin_bit_cast(u32x2, v0), a1 = __builtin_bit_cast(u32x2, v1);
-                const u32x4 aw = {a0[0], a0[1], a1[0], a1[1]};
-                return __builtin_bit_cast(bf16x8, aw);
-            };
-#pragma unroll
-            for (int db = 0; db < DB; ++db) fa[db] = ldv1(0, db);
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int c = i >> 2, db = i & 3;
-                const u32x4 pw = {pk[4 * c], pk[4 * c + 1], pk[4 * c + 2], pk[4 * c + 3]};
-                ot[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[db], __builtin_bit_cast(bf16x8, pw), ot[db], 0, 0, 0);
-                if (c < 3) fa[db] = ldv1(c + 1, db);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        };
-        // softmax of the tile in st into pk, lk (and mnew_k, alpha_k for an exact-max tile); m2, lsum, ot are left alone
-        auto spec_softmax = [&](int j, auto special_c, auto fast_c) __attribute__((always_inline)) {
-            constexpr bool SPECIAL = decltype(special_c)::value, FAST = decltype(fast_c)::value;
-            float mt = m2;
-            lk = 0.f;
-            if (FAST) softmax_tile<SPECIAL, false, DB, false>(st, pk, ot, mt, lk, p.c, j * BN, limit, hh);
-            else softmax_tile<SPECIAL, true, DB, false>(st, pk, ot, mt, lk, p.c, j * BN, tile_masked(j) ? limit : 0x3fffffff, hh);
-            mnew_k = mt;
-            alpha_k = SPECIAL ? __builtin_amdgcn_exp2f(m2 - (mt == -INFINITY ? 0.f : mt)) : 1.f;
-        };
-        // decision on the previous visit (its votes were cast a barrier ago), then commit or drop
-        // PS: was the previous visit an exact-max one?  0 = no, 1 = yes, 2 = look at prev_special (the steady loops
-        // know the answer at compile time and so carry no rescale of the 64 accumulator registers at all)
-        auto resolve = [&](auto ps_c) __attribute__((always_inline)) {
-            constexpr int PS = decltype(ps_c)::value;
-            bool keep = false;
-            if (have_prev) {
-                const int kp = (j_prev >> 16) & 1;  // parity of the previous visit
-                keep = __builtin_amdgcn_readfirstlane(votes[kp][grp][0] | votes[kp][grp][1] | votes[kp][grp][2] |
-                                                      votes[kp][grp][3]) != 0;
-                const int j = j_prev & 0xffff;
-                if (mrow && j <= j_hi_g && (tid & 255) == 0) mrow[j] = keep ? 0 : 1;  // (a tile past j_hi_g is the other block's)
-                if (keep) {
-                    if (PS == 1 || (PS == 2 && prev_special)) {
-                        lsum = lsum * alpha_k + lk;
-#pragma unroll
-                        for (int db = 0; db < DB; ++db) ot[db] *= alpha_k;
-                        m2 = mnew_k;
-                    } else {
-                        lsum += lk;
-                    }
-                }
-            }
-            return keep;
-        };
-        auto matrix_vsa = [&](int k, auto ps_c) __attribute__((always_inline)) {
-            const uint8_t* kt = Ks + (k & 3) * T::BYTES;
-            asm volatile("" : "+v"(kb));
-            auto ldk1 = [&](int i) __attribute__((always_inline)) {  // fragment i = (k-step i / 2, key half i % 2)
-                return *reinterpret_cast<const bf16x8*>(kt + (kb ^ ((i >> 1) << 5)) + (i & 1) * 32 * T::ROWB);
-            };
-            __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) fa[i] = ldk1(i);  // in flight while the decision is read
-            const bool keep = resolve(ps_c);
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                st[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i & 3], qf[i >> 1], i < 2 ? f32x16{0} : st[i & 1], 0, 0, 0);
-                if (i + 4 < 16) fa[i & 3] = ldk1(i + 4);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            vote(k);
-            __builtin_amdgcn_sched_barrier(0);
-            if (keep) pv_prev(k - 1);
-            __builtin_amdgcn_s_setprio(0);
-        };
-        // speculative softmax of visit k: st -> pk, lk (and mnew_k, alpha_k); m2, lsum, ot are left alone
-        auto vector_vsa = [&](int k, auto special_c, auto fast_c) __attribute__((always_inline)) {
-            constexpr bool SPECIAL = decltype(special_c)::value, FAST = decltype(fast_c)::value;
-            const int j = vis.tile(k);
-            fetch_ahead(k);
-            spec_softmax(j, special_c, fast_c);
-            prev_special = SPECIAL;
-            have_prev = true;
-            j_prev = j | ((k & 1) << 16);
-        };
-        // block pairs: a local tile is exact-max only for the group whose block it belongs to
-        auto own_special = [&](int k) __attribute__((always_inline)) {
-            return !pb || k < vis.n1 || ((k - vis.n1 < vis.n2b) == (grp == 1));
-        };
-        // Both groups run M(0) V(0) M(1) V(1) ...; group 0 passes the barrier after each vector phase, group 1
-        // after each matrix phase, which puts group 1 half an interval behind as in the other modes.
-        using PS0 = std::integral_constant<int, 0>;
-        using PS2 = std::integral_constant<int, 2>;
-        // (one copy of the loop nest per group, as in the other modes: straight-line code for the register allocator)
-        auto run_vsa = [&](auto grp_c) __attribute__((always_inline)) {
-            constexpr int GRP = decltype(grp_c)::value;
-            auto step = [&](int k, auto ps_c, auto special_c, auto fast_c) __attribute__((always_inline)) {
-                matrix_vsa(k, ps_c);
-                if (GRP == 1) __builtin_amdgcn_s_barrier();
-                __builtin_amdgcn_sched_barrier(0);
-                vector_vsa(k, special_c, fast_c);
-                if (GRP == 0) __builtin_amdgcn_s_barrier();
-                __builtin_amdgcn_sched_barrier(0);
-            };
-            int k = 0;
-            for (; k < min(n_lead, nv); ++k) {
-                if (own_special(k)) step(k, PS2{}, true_type{}, false_type{});
-                else step(k, PS2{}, false_type{}, false_type{});
-            }
-            if (k < nv) {  // the first frozen visit still has an exact-max visit to resolve
-                step(k, PS2{}, false_type{}, false_type{});
-                ++k;
-            }
-            for (; k < k_fast_end; ++k) step(k, PS0{}, false_type{}, true_type{});
-            for (; k < nv; ++k) step(k, PS0{}, false_type{}, false_type{});
-            if (resolve(PS2{})) pv_prev(nv - 1);  // the last visit's decision (its votes are a barrier old for both groups)
-            store_output<D>(p, ot, m2, lsum, b, h, qrow, hh);
-        };
-        if (grp == 0) run_vsa(std::integral_constant<int, 0>{});
-        else run_vsa(std::integral_constant<int, 1>{});
-    } else {
+    {
         if (grp == 0) run_group(std::integral_constant<int, 0>{});
         else run_group(std::integral_constant<int, 1>{});
     }

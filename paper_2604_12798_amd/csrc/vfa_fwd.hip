@@ -10,6 +10,7 @@
 #include "common.hpp"
 #include "attn_generic.hpp"
 #include "attn_pingpong.hpp"
+#include "attn_vsa.hpp"
 #include "summary.hpp"
 #include "decode.hpp"
 #include "fp8.hpp"
@@ -85,7 +86,11 @@ int launch_fwd(const Params& p, int d, int block_m, hipStream_t s) {
         !(MODE == MODE_VSA && p.tau2 >= 0.f) &&
         (head_pairs || MODE != MODE_VSA || (p.causal && p.n_local <= 1))) {
         static std::atomic<unsigned char> lds_raised[kMaxDevices];  // one set of flags per instantiation
-        if (!raise_lds_limit(&attn_fwd_pp_kernel<MODE>, PP_LDS_BYTES, lds_raised)) return VFA_ERR_HIP;
+        if constexpr (MODE == MODE_VSA) {
+            if (!raise_lds_limit(&attn_vsa_pp_kernel, VSA_LDS_BYTES, lds_raised)) return VFA_ERR_HIP;
+        } else {
+            if (!raise_lds_limit(&attn_fwd_pp_kernel<MODE>, PP_LDS_BYTES, lds_raised)) return VFA_ERR_HIP;
+        }
         Params q = p;
         q.pair_blocks = head_pairs ? 0 : 1;
         unsigned n_wg = (unsigned)(head_pairs ? p.B * (p.Hq / 2) * p.Tr : p.B * p.Hq * ((p.Tr + 1) / 2));
@@ -98,7 +103,8 @@ int launch_fwd(const Params& p, int d, int block_m, hipStream_t s) {
             n_wg = (unsigned)n_cu;
         }
         const dim3 grid_pp(n_wg);
-        attn_fwd_pp_kernel<MODE><<<grid_pp, 512, PP_LDS_BYTES, s>>>(q);
+        if constexpr (MODE == MODE_VSA) attn_vsa_pp_kernel<<<grid_pp, 512, VSA_LDS_BYTES, s>>>(q);
+        else attn_fwd_pp_kernel<MODE><<<grid_pp, 512, PP_LDS_BYTES, s>>>(q);
         return hipGetLastError() == hipSuccess ? VFA_OK : VFA_ERR_HIP;
     }
     const dim3 grid((unsigned)(p.B * p.Hq * p.Tr));
