@@ -5,56 +5,66 @@
 namespace {
 
 // ---------------------------------------------------------------------------------------------
-// Key-block summary: one workgroup per (b*Hkv + h, j); signed element of largest magnitude per
-// dimension over the block's keys, ties to the positive value.  Works on bf16 bit patterns:
-// magnitude order = order of (bits & 0x7fff); on equal magnitude the smaller pattern is the
-// positive one.
-__device__ inline uint32_t sabs_pick(uint32_t a, uint32_t b) {  // one bf16 in the low 16 bits
-    const uint32_t ma = a & 0x7fffu, mb = b & 0x7fffu;
-    return ma > mb ? a : (mb > ma ? b : min(a, b));
-}
-__device__ inline uint32_t sabs_pick2(uint32_t a, uint32_t b) {  // two packed bf16
-    return sabs_pick(a & 0xffffu, b & 0xffffu) | (sabs_pick(a >> 16, b >> 16) << 16);
+// Key-block summary (Alg. 1, first loop): per dimension the element of largest magnitude of the block's keys with its
+// sign, ties to the positive value.  HBM bound: K is read once.  One WAVE per key block, four blocks per workgroup:
+// a lane owns one 16-byte chunk of every RG-th row, issues its loads eight at a time (no loop-carried dependence
+// between them), reduces in registers, and the RG lanes of a chunk combine through lane exchanges: no LDS, no
+// barrier, 128 bytes per lane in flight.
+// Works on bf16 bit patterns, two to a dword: the key (magnitude << 1) | (sign ? 0 : 1) orders elements by magnitude
+// and, at equal magnitude, puts the positive one on top, so the pick is an unsigned 16-bit maximum of keys.
+typedef __attribute__((ext_vector_type(2))) unsigned short u16x2;
+__device__ inline uint32_t sabs_key(uint32_t x) { return ((x << 1) & 0xfffefffeu) | ((~x >> 15) & 0x00010001u); }
+__device__ inline uint32_t sabs_unkey(uint32_t k) { return ((k >> 1) & 0x7fff7fffu) | ((~k & 0x00010001u) << 15); }
+__device__ inline uint32_t key_max(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b)));
 }
 
 // N = row stride of one head's key array (its capacity), n_valid = keys present, Tc = block stride of
-// one head's summary array, j0 = first block to (re)compute: a growing cache recomputes only the
-// blocks that received keys.
+// one head's summary array, j0 = first block to (re)compute and n_blocks their number: a growing cache
+// recomputes only the blocks that received keys.
 // With per-sequence lengths (old_len / new_len device arrays indexed by batch entry, Hkv heads per entry) the
-// grid covers every block of the capacity and a workgroup whose block received no key returns at once.
+// grid covers every block of the capacity and a wave whose block received no key returns at once.
 template <int D>
 __global__ __launch_bounds__(256) void kblock_summary_kernel(const uint16_t* __restrict__ K, uint16_t* __restrict__ R,
-                                                             int N, int n_valid, int Tc, int block_n, int j0,
+                                                             int N, int n_valid, int Tc, int block_n, int j0, int n_blocks,
                                                              const int* __restrict__ old_len = nullptr,
                                                              const int* __restrict__ new_len = nullptr, int Hkv = 1) {
     constexpr int CH = D / 8;        // 16-byte chunks per row
-    constexpr int RG = 256 / CH;     // row groups
-    __shared__ u32x4 part[RG][CH];
-    const int j = j0 + blockIdx.x, bh = blockIdx.y;
+    constexpr int RG = 64 / CH;      // rows a wave reads at once
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int jb = blockIdx.x * 4 + wave, bh = blockIdx.y;
+    if (jb >= n_blocks) return;
+    const int j = j0 + jb;
     if (new_len) {
         const int b = bh / Hkv;
         const int n_new = min(max(new_len[b], 0), N), n_old = min(max(old_len[b], 0), n_new);
-        if (j < n_old / block_n || j * block_n >= n_new) return;  // (uniform over the workgroup)
+        if (j < n_old / block_n || j * block_n >= n_new) return;  // (uniform over the wave)
         n_valid = n_new;
     }
-    const int ch = threadIdx.x % CH, rg = threadIdx.x / CH;
+    const int ch = lane % CH, rg = lane / CH;
     const int c0 = j * block_n, c1 = min(n_valid, c0 + block_n);
-    const uint16_t* base = K + (size_t)bh * N * D;
-    u32x4 acc = {0, 0, 0, 0};
-    for (int r = c0 + rg; r < c1; r += RG) {
-        const u32x4 x = *reinterpret_cast<const u32x4*>(base + (size_t)r * D + ch * 8);
+    const uint16_t* base = K + (size_t)bh * N * D + ch * 8;
+    const uint32_t zero_key = sabs_key(0u);  // +0: the smallest magnitude, already the positive one
+    u32x4 acc = {zero_key, zero_key, zero_key, zero_key};
+    for (int r0 = c0 + rg; r0 < c1; r0 += 8 * RG) {
+        u32x4 x[8];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[e] = sabs_pick2(acc[e], x[e]);
-    }
-    part[rg][ch] = acc;
-    __syncthreads();
-    if (rg == 0) {
-        for (int q = 1; q < RG; ++q) {
-            const u32x4 x = part[q][ch];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) acc[e] = sabs_pick2(acc[e], x[e]);
+        for (int u = 0; u < 8; ++u) {
+            const int r = r0 + u * RG;
+            x[u] = r < c1 ? *reinterpret_cast<const u32x4*>(base + (size_t)r * D) : u32x4{0, 0, 0, 0};
         }
-        *reinterpret_cast<u32x4*>(R + ((size_t)bh * Tc + j) * D + ch * 8) = acc;
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] = key_max(acc[e], sabs_key(x[u][e]));
+    }
+#pragma unroll
+    for (int m = CH; m < 64; m <<= 1)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] = key_max(acc[e], (uint32_t)__shfl_xor((int)acc[e], m));
+    if (rg == 0) {
+        const u32x4 out = {sabs_unkey(acc[0]), sabs_unkey(acc[1]), sabs_unkey(acc[2]), sabs_unkey(acc[3])};
+        *reinterpret_cast<u32x4*>(R + ((size_t)bh * Tc + j) * D + ch * 8) = out;
     }
 }
 

@@ -119,12 +119,13 @@ int launch_fwd(const Params& p, int d, int block_m, hipStream_t s) {
 int summary_launch(const void* K, void* Krepr, int B, int Hkv, int N, int d, int block_n, int repr_mode, hipStream_t s) {
     const int Tc = ceil_div(N, block_n);
     const dim3 grid((unsigned)Tc, (unsigned)(B * Hkv));
+    const dim3 grid4((unsigned)ceil_div(Tc, 4), (unsigned)(B * Hkv));  // sabsmax: one wave per block, four to a workgroup
     const uint16_t* k = (const uint16_t*)K;
     uint16_t* r = (uint16_t*)Krepr;
     (void)hipGetLastError();
     if (repr_mode == 0) {
-        if (d == 128) kblock_summary_kernel<128><<<grid, 256, 0, s>>>(k, r, N, N, Tc, block_n, 0);
-        else kblock_summary_kernel<64><<<grid, 256, 0, s>>>(k, r, N, N, Tc, block_n, 0);
+        if (d == 128) kblock_summary_kernel<128><<<grid4, 256, 0, s>>>(k, r, N, N, Tc, block_n, 0, Tc);
+        else kblock_summary_kernel<64><<<grid4, 256, 0, s>>>(k, r, N, N, Tc, block_n, 0, Tc);
     } else {
         if (d == 128) kblock_summary_alt_kernel<128><<<grid, 256, 0, s>>>(k, r, N, Tc, block_n, repr_mode);
         else kblock_summary_alt_kernel<64><<<grid, 256, 0, s>>>(k, r, N, Tc, block_n, repr_mode);
@@ -314,13 +315,13 @@ int vfa_kblock_summary_append(const void* K, void* Krepr, int B, int Hkv, int n_
     if ((long long)B * Hkv > 65535) return VFA_ERR_UNSUPPORTED;
     const int j0 = n_old / block_n, j1 = ceil_div(n_new, block_n);  // blocks [j0, j1) received keys
     const int tc_cap = ceil_div(n_cap, block_n);
-    const dim3 grid((unsigned)(j1 - j0), (unsigned)(B * Hkv));
+    const dim3 grid((unsigned)ceil_div(j1 - j0, 4), (unsigned)(B * Hkv));
     hipStream_t s = (hipStream_t)stream;
     (void)hipGetLastError();
     if (d == 128)
-        kblock_summary_kernel<128><<<grid, 256, 0, s>>>((const uint16_t*)K, (uint16_t*)Krepr, n_cap, n_new, tc_cap, block_n, j0);
+        kblock_summary_kernel<128><<<grid, 256, 0, s>>>((const uint16_t*)K, (uint16_t*)Krepr, n_cap, n_new, tc_cap, block_n, j0, j1 - j0);
     else
-        kblock_summary_kernel<64><<<grid, 256, 0, s>>>((const uint16_t*)K, (uint16_t*)Krepr, n_cap, n_new, tc_cap, block_n, j0);
+        kblock_summary_kernel<64><<<grid, 256, 0, s>>>((const uint16_t*)K, (uint16_t*)Krepr, n_cap, n_new, tc_cap, block_n, j0, j1 - j0);
     return hipGetLastError() == hipSuccess ? VFA_OK : VFA_ERR_HIP;
 }
 
@@ -372,13 +373,13 @@ int vfa_kblock_summary_append_varlen(const void* K, void* Krepr, int B, int Hkv,
     if ((reinterpret_cast<uintptr_t>(old_lens) | reinterpret_cast<uintptr_t>(new_lens)) & 3u) return VFA_ERR_INVALID_ARG;
     if ((long long)B * Hkv > 65535) return VFA_ERR_UNSUPPORTED;
     const int tc_cap = ceil_div(n_cap, block_n);
-    const dim3 grid((unsigned)tc_cap, (unsigned)(B * Hkv));
+    const dim3 grid((unsigned)ceil_div(tc_cap, 4), (unsigned)(B * Hkv));
     hipStream_t s = (hipStream_t)stream;
     (void)hipGetLastError();
     if (d == 128)
-        kblock_summary_kernel<128><<<grid, 256, 0, s>>>((const uint16_t*)K, (uint16_t*)Krepr, n_cap, 0, tc_cap, block_n, 0, old_lens, new_lens, Hkv);
+        kblock_summary_kernel<128><<<grid, 256, 0, s>>>((const uint16_t*)K, (uint16_t*)Krepr, n_cap, 0, tc_cap, block_n, 0, tc_cap, old_lens, new_lens, Hkv);
     else
-        kblock_summary_kernel<64><<<grid, 256, 0, s>>>((const uint16_t*)K, (uint16_t*)Krepr, n_cap, 0, tc_cap, block_n, 0, old_lens, new_lens, Hkv);
+        kblock_summary_kernel<64><<<grid, 256, 0, s>>>((const uint16_t*)K, (uint16_t*)Krepr, n_cap, 0, tc_cap, block_n, 0, tc_cap, old_lens, new_lens, Hkv);
     return hipGetLastError() == hipSuccess ? VFA_OK : VFA_ERR_HIP;
 }
 
