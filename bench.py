@@ -62,33 +62,54 @@ def time_sustained(fn, seconds=1.0, chunk=20):
     return a.elapsed_time(b) / n, n
 
 
-def mfma_ceiling(torch, dev, seed):
-    """The MFMA-only probe (bench_mfma_probe.hip, a library of its own): bf16 32x32x16 MFMAs on register operands,
-    two waves per SIMD as in the attention kernel, once on normally distributed operands and once on zeros."""
-    path = os.path.join(ROOT, "bench_mfma_probe.so")
+def ceilings(torch, dev, seed):
+    """The probe library (bench_probes.hip, a library of its own): MFMAs on register operands, two waves per SIMD as in
+    the attention kernels (bf16 32x32x16 and E4M3 32x32x64), once on normally distributed operands and once on zeros
+    (the clock the chip grants follows how many operand bits toggle), and a streaming read of 512 MiB."""
+    path = os.path.join(ROOT, "bench_probes.so")
     if not os.path.exists(path):
         raise RuntimeError(f"{path} is missing: build it with `python -m paper_2604_12798_amd.build`")
     P = ctypes.CDLL(path)
+    vp, ci = ctypes.c_void_p, ctypes.c_int
     P.mfma_probe_data_elems.restype = ctypes.c_size_t
+    P.mfma_fp8_probe_data_bytes.restype = ctypes.c_size_t
     P.mfma_probe_flop.restype = ctypes.c_double
-    P.mfma_probe_flop.argtypes = [ctypes.c_int, ctypes.c_int]
-    P.mfma_probe_launch.restype = ctypes.c_int
-    P.mfma_probe_launch.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
-    n = int(P.mfma_probe_data_elems())
+    P.mfma_probe_flop.argtypes = [ci, ci]
+    for f in (P.mfma_probe_launch, P.mfma_fp8_probe_launch):
+        f.restype = ci
+        f.argtypes = [vp, vp, ci, ci, vp]
+    P.hbm_read_probe_launch.restype = ci
+    P.hbm_read_probe_launch.argtypes = [vp, vp, ctypes.c_size_t, ci, vp]
     g = torch.Generator(device="cpu").manual_seed(seed)
     blocks = torch.cuda.get_device_properties(0).multi_processor_count
-    iters = 6000      # 96000 MFMAs per wave: about 4 ms per launch
     outb = torch.empty(blocks * 512, dtype=torch.float32, device=dev)
+    stream = lambda: vp(torch.cuda.current_stream().cuda_stream)
     res = {}
+
+    def timed(launch):
+        def run():
+            if launch() != 0:
+                raise RuntimeError("probe launch failed")
+        return time_region(run, 40, 10)
+
+    n = int(P.mfma_probe_data_elems())
+    iters = 6000      # 96000 MFMAs per wave: about 4 ms per launch
     for what, data in (("normal", torch.randn(n, generator=g).to(torch.bfloat16).to(dev)),
                        ("zeros", torch.zeros(n, dtype=torch.bfloat16, device=dev))):
-        def run():
-            rc = P.mfma_probe_launch(ctypes.c_void_p(data.data_ptr()), ctypes.c_void_p(outb.data_ptr()), blocks, iters,
-                                     ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
-            if rc != 0:
-                raise RuntimeError("mfma probe launch failed")
-        ms = time_region(run, 40, 10)
-        res[what] = float(P.mfma_probe_flop(blocks, iters)) / ms / 1e9
+        ms = timed(lambda: P.mfma_probe_launch(vp(data.data_ptr()), vp(outb.data_ptr()), blocks, iters, stream()))
+        res["bf16_" + what] = float(P.mfma_probe_flop(blocks, iters)) / ms / 1e9
+    n8 = int(P.mfma_fp8_probe_data_bytes())
+    e4m3 = getattr(torch, "float8_e4m3fn")
+    for what, data in (("normal", torch.randn(n8, generator=g).to(dev).to(e4m3).view(torch.uint8)),
+                       ("zeros", torch.zeros(n8, dtype=torch.uint8, device=dev))):
+        ms = timed(lambda: P.mfma_fp8_probe_launch(vp(data.data_ptr()), vp(outb.data_ptr()), blocks, iters // 2, stream()))
+        res["fp8_" + what] = 4.0 * float(P.mfma_probe_flop(blocks, iters // 2)) / ms / 1e9
+    nbytes = 512 << 20
+    buf = torch.empty(nbytes, dtype=torch.uint8, device=dev).random_(generator=None)
+    rblocks = blocks * 8
+    outr = torch.empty(rblocks * 256, dtype=torch.int32, device=dev)
+    ms = timed(lambda: P.hbm_read_probe_launch(vp(buf.data_ptr()), vp(outr.data_ptr()), nbytes, rblocks, stream()))
+    res["hbm_read_GB/s"] = nbytes / ms / 1e6
     return res
 
 
@@ -304,12 +325,14 @@ def main():
         out["frozen_tile_fraction"] = frozen_tile_fraction(w)
     if "ceiling" in only:
         # what the matrix cores alone deliver on this machine at the clock the chip grants them (operands in registers)
-        c = mfma_ceiling(torch, dev, args.seed)
-        out["mfma_ceiling"] = {"tflops_normal_operands": c["normal"], "tflops_zero_operands": c["zeros"],
-                               "kernel": "bench_mfma_probe.hip: v_mfma_f32_32x32x16_bf16 only, 2 waves per SIMD"}
+        c = ceilings(torch, dev, args.seed)
+        out["mfma_ceiling"] = {"tflops_normal_operands": c["bf16_normal"], "tflops_zero_operands": c["bf16_zeros"],
+                               "fp8_tflops_normal_operands": c["fp8_normal"], "fp8_tflops_zero_operands": c["fp8_zeros"],
+                               "kernel": "bench_probes.hip: MFMAs only (bf16 32x32x16, E4M3 32x32x64), 2 waves per SIMD"}
+        out["hbm_read_ceiling_GB/s"] = c["hbm_read_GB/s"]
         if "vfa" in only:
-            out["pct_of_measured_ceiling"] = 100.0 * out["value"] / c["normal"]
-            out["roofline"]["frac_of_measured_ceiling"] = out["roofline"]["achieved"] / c["normal"]
+            out["pct_of_measured_ceiling"] = 100.0 * out["value"] / c["bf16_normal"]
+            out["roofline"]["frac_of_measured_ceiling"] = out["roofline"]["achieved"] / c["bf16_normal"]
     if "summary" in only:
         ms_s = time_region(run_summary, args.steps, args.warmup)
         kbytes = w.B * w.Hkv * w.N * w.d * 2 * (1 + 1.0 / w.block_n)
@@ -397,6 +420,13 @@ def main():
         out["vsa_cfg5"] = vsa_on_cfg5(args, torch, vfa)
     if "decode" in only:
         out["decode"] = decode_step(args, torch, vfa)
+    if "ceiling" in only:
+        if "fp8" in out:
+            out["fp8"]["frac_vfa_of_measured_ceiling"] = out["fp8"]["vfa_tflops"] / out["mfma_ceiling"]["fp8_tflops_normal_operands"]
+        if "decode" in out:
+            out["decode"]["frac_of_measured_read_ceiling"] = out["decode"]["achieved_GB/s"] / out["hbm_read_ceiling_GB/s"]
+        if "kblock_summary" in out:
+            out["kblock_summary"]["frac_of_measured_read_ceiling"] = out["kblock_summary"]["GB/s"] / out["hbm_read_ceiling_GB/s"]
     out["paper_context"] = ("paper reports no measured kernel throughput; its analytic model gives ~2x for C8V32/C4V32/C4V16 "
                             "over C16V32 and 1.00x for VFA vs FA at C16V32 (the bf16 analogue) on its own accelerator")
     if not args.no_cpu_baseline:

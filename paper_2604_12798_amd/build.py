@@ -19,8 +19,8 @@ HIPCC_FLAGS = [
 ]
 
 
-PROBE_SRC = os.path.join(ROOT, "bench_mfma_probe.hip")   # bench.py's MFMA-only ceiling probe: a library of its own
-PROBE_LIB = os.path.join(ROOT, "bench_mfma_probe.so")
+PROBE_SRC = os.path.join(ROOT, "bench_probes.hip")   # bench.py's ceiling probes (MFMA only, HBM read only): a library of its own
+PROBE_LIB = os.path.join(ROOT, "bench_probes.so")
 
 
 def _run(cmd: list[str], verbose: bool) -> None:
