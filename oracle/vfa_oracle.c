@@ -238,11 +238,13 @@ int oracle_visit_list(int N, int block_m, int block_n, int causal, int i, int n_
 typedef struct {
     int n_sink, n_local, use_minit, reorder, freeze, vsa;
     double ln_lambda;
-    double lazy_tau; /* < 0: off; else keep the old max while it grows by at most lazy_tau * ln 2 */
-    int rowskip;     /* with vsa: rows that fail the threshold test drop out of a kept tile */
     const double *qrepr; /* NULL, or [B,Hq,Tr,d]: one summary vector per query block replaces the rows of
-                          * Q_i in the approximate score (ablation "block-wise approximation on Q") */
+                          * Q_i in the approximate score (the ablation that approximates block-wise on Q) */
 } opts_t;
+
+/* One query block of Alg. 1 (VFA), Alg. 2 (VSA: vsa = 1) or the FA column of Table 1 (freeze = 0,
+ * ascending order, no seed), in the algorithms' order of steps.  The appendix variants with their
+ * extra rules live in one_block_variant below. */
 
 static void one_block(const prob_t *p, const opts_t *o, const double *krepr, int b, int h, int i,
                       const double *m_override, double *O, double *LSE, double *m_init_out,
@@ -318,39 +320,12 @@ static void one_block(const prob_t *p, const opts_t *o, const double *krepr, int
             if (worst < o->ln_lambda) {
                 if (mask_row) mask_row[j] = 1;
                 counters[3] += 1; /* skipped tiles */
-                if (o->rowskip) counters[2] += nr; /* (row-skip runs report suppressed rows here) */
                 if (traj) for (int rr = 0; rr < nr; ++rr) { traj[((size_t)k * Br + rr) * 2] = m[rr]; traj[((size_t)k * Br + rr) * 2 + 1] = l[rr]; }
                 continue;
             }
-            if (o->rowskip) {
-                /* Blasst_Rowskip: in a tile that is kept, a row that fails the same test contributes
-                 * nothing: its scores become -inf (zero mass) and its state does not move */
-                for (int rr = 0; rr < nr; ++rr) {
-                    const double diff = (mt[rr] == -INFINITY) ? -INFINITY : mt[rr] - fmax(m[rr], mt[rr]);
-                    if (diff < o->ln_lambda) {
-                        for (int cc = 0; cc < nc; ++cc) S[rr * Bc + cc] = -INFINITY;
-                        mt[rr] = -INFINITY;
-                        counters[2] += 1;
-                    }
-                }
-            }
         }
         if (mask_row) mask_row[j] = 0;
-        if (special && o->lazy_tau >= 0.0) {
-            /* conditional rescale (the rescale-skip rule of the Blasst_FA4 variant): a row whose max
-             * grew by at most tau * ln 2 keeps its old max, so its scale factor is 1; the rescale chain
-             * of the tile counts as executed only if some row did change its max */
-            int any = 0;
-            for (int rr = 0; rr < nr; ++rr) {
-                const double m_new = fmax(m[rr], mt[rr]);
-                const int keep_old = (m[rr] != -INFINITY) && (m_new - m[rr] <= o->lazy_tau * 0.69314718055994530942);
-                if (keep_old) mt[rr] = -INFINITY; /* row takes max(m, -inf) = m below */
-                else if (m_new != m[rr]) any = 1;
-            }
-            counters[2] += any;
-        } else if (special && !o->rowskip) {
-            counters[2] += 1; /* rescale chain executed on this tile */
-        }
+        if (special) counters[2] += 1; /* rescale chain executed on this tile */
         for (int rr = 0; rr < nr; ++rr) {
             double m_use = m[rr], alpha = 1.0;
             if (special) {
@@ -438,7 +413,7 @@ int oracle_blocks_qrepr(const float *Q, const float *K, const float *V, int B, i
     if (Hq % Hkv != 0 || block_m <= 0 || block_n <= 0) return -1;
     if (use_minit && !krepr && !m_override) return -1;
     prob_t p = {Q, K, V, B, Hq, Hkv, N, d, block_m, block_n, causal, scale};
-    opts_t o = {n_sink, n_local, use_minit, reorder, freeze, vsa, ln_lambda, -1.0, 0, qrepr};
+    opts_t o = {n_sink, n_local, use_minit, reorder, freeze, vsa, ln_lambda, qrepr};
     const int Tc = ceil_div(N, block_n);
 #pragma omp parallel for schedule(dynamic, 1)
     for (int n = 0; n < nblk; ++n) {
@@ -456,6 +431,100 @@ int oracle_blocks_qrepr(const float *Q, const float *K, const float *V, int B, i
     return 0;
 }
 
+/* ------------------------------------------------------------------ */
+/* One query block of the appendix's sparse-attention variants, all built on plain online softmax
+ * (key blocks in ascending order, exact-max update on every block, no seed):
+ *   skip     1 = the BLASST test before every block (vanilla BLASST): drop the block iff
+ *            m~ - max(m, m~) < ln(lambda) for all rows
+ *   rowskip  Blasst_Rowskip: in a block that is kept, a row that fails the same test contributes
+ *            nothing (zero mass) and its state does not move
+ *   lazy_tau >= 0: Blasst_FA4's rescale-skip rule: a row adopts the new max only when it exceeds
+ *            the old one by more than lazy_tau * ln 2; otherwise it keeps the old max (scale factor 1)
+ * Shares only score(), the row accessors and the block geometry with one_block.
+ * counters: [0] blocks visited, [1] row-max executions, [2] blocks whose rescale chain ran (rowskip:
+ * rows suppressed instead, a skipped block counting all its rows), [3] blocks skipped.            */
+static void one_block_variant(const prob_t *p, int skip, double ln_lambda, int rowskip, double lazy_tau,
+                              int b, int h, int i, double *O, double *LSE, uint8_t *mask_row,
+                              double *margin_row, int64_t *counters) {
+    const int N = p->N, d = p->d, Br = p->block_m, Bc = p->block_n;
+    const int Tc = ceil_div(N, Bc);
+    const int r0 = i * Br, nr = imin(Br, N - r0);
+    int a_lo, a_hi, j_hi;
+    geometry(N, Br, Bc, p->causal, i, &a_lo, &a_hi, &j_hi);
+    double *m = (double *)malloc((size_t)Br * sizeof(double));
+    double *l = (double *)calloc((size_t)Br, sizeof(double));
+    double *acc = (double *)calloc((size_t)Br * d, sizeof(double));
+    double *S = (double *)malloc((size_t)Br * Bc * sizeof(double));
+    double *mt = (double *)malloc((size_t)Br * sizeof(double));
+    int *live = (int *)malloc((size_t)Br * sizeof(int)); /* row takes part in this block */
+    for (int rr = 0; rr < Br; ++rr) m[rr] = -INFINITY;
+    if (mask_row) for (int j = 0; j < Tc; ++j) mask_row[j] = 2;
+    if (margin_row) for (int j = 0; j < Tc; ++j) margin_row[j] = NAN;
+
+    for (int j = 0; j <= j_hi; ++j) {
+        const int c0 = j * Bc, nc = imin(Bc, N - c0);
+        for (int rr = 0; rr < nr; ++rr) {
+            double x = -INFINITY;
+            for (int cc = 0; cc < nc; ++cc) {
+                const int r = r0 + rr, c = c0 + cc;
+                const double sc = (p->causal && c > r) ? -INFINITY : score(p, b, h, r, c);
+                S[rr * Bc + cc] = sc;
+                x = fmax(x, sc);
+            }
+            mt[rr] = x;
+            live[rr] = 1;
+        }
+        counters[0] += 1;
+        counters[1] += 1;
+        if (skip) {
+            double worst = -INFINITY;
+            for (int rr = 0; rr < nr; ++rr) {
+                const double diff = (mt[rr] == -INFINITY) ? -INFINITY : mt[rr] - fmax(m[rr], mt[rr]);
+                if (rowskip && diff < ln_lambda) live[rr] = 0;
+                worst = fmax(worst, diff);
+            }
+            if (margin_row) margin_row[j] = worst - ln_lambda;
+            if (worst < ln_lambda) {
+                if (mask_row) mask_row[j] = 1;
+                counters[3] += 1;
+                if (rowskip) counters[2] += nr;
+                continue;
+            }
+            if (rowskip)
+                for (int rr = 0; rr < nr; ++rr) counters[2] += live[rr] ? 0 : 1;
+        }
+        if (mask_row) mask_row[j] = 0;
+        int rescaled = 0;
+        for (int rr = 0; rr < nr; ++rr) {
+            if (!live[rr]) continue;
+            double m_new = fmax(m[rr], mt[rr]);
+            if (lazy_tau >= 0.0 && m[rr] != -INFINITY && m_new - m[rr] <= lazy_tau * 0.69314718055994530942)
+                m_new = m[rr]; /* the max grew too little to be worth a rescale */
+            if (m_new != m[rr]) rescaled = 1;
+            const double alpha = (m_new == -INFINITY) ? 1.0 : exp(m[rr] - m_new);
+            double *orow = acc + (size_t)rr * d;
+            for (int t = 0; t < d; ++t) orow[t] *= alpha;
+            l[rr] *= alpha;
+            double rowsum = 0.0;
+            for (int cc = 0; cc < nc; ++cc) {
+                const double sc = S[rr * Bc + cc];
+                const double pt = (sc == -INFINITY) ? 0.0 : exp(sc - m_new);
+                rowsum += pt;
+                const float *v = v_row(p, b, h, c0 + cc);
+                for (int t = 0; t < d; ++t) orow[t] += pt * (double)v[t];
+            }
+            l[rr] += rowsum; /* (the block's mass first, then onto l: the order of Table 1's rowsum step) */
+            m[rr] = m_new;
+        }
+        if (!rowskip) counters[2] += (lazy_tau >= 0.0) ? rescaled : 1;
+    }
+    for (int rr = 0; rr < nr; ++rr) {
+        for (int t = 0; t < d; ++t) O[(size_t)rr * d + t] = (l[rr] > 0.0) ? acc[(size_t)rr * d + t] / l[rr] : 0.0;
+        LSE[rr] = (l[rr] > 0.0) ? m[rr] + log(l[rr]) : -INFINITY;
+    }
+    free(m); free(l); free(acc); free(S); free(mt); free(live);
+}
+
 /* Online softmax with the conditional rescale of the "Blasst_FA4" variant (its second stage
  * alone, no block skipping): ascending order, row max on every block, but a row adopts the
  * new max only when it exceeds the old one by more than tau * ln 2; otherwise the old max is
@@ -467,13 +536,12 @@ int oracle_fa_lazy(const float *Q, const float *K, const float *V, int B, int Hq
                    const int *blocks, double *O, double *LSE, int64_t *counters) {
     if (Hq % Hkv != 0 || block_m <= 0 || block_n <= 0 || !(tau >= 0.0)) return -1;
     prob_t p = {Q, K, V, B, Hq, Hkv, N, d, block_m, block_n, causal, scale};
-    opts_t o = {0, 0, 0, 0, 0, 0, 0.0, tau, 0};
 #pragma omp parallel for schedule(dynamic, 1)
     for (int n = 0; n < nblk; ++n) {
         int64_t *cn = counters + (size_t)n * 4;
         cn[0] = cn[1] = cn[2] = cn[3] = 0;
-        one_block(&p, &o, NULL, blocks[3 * n], blocks[3 * n + 1], blocks[3 * n + 2], NULL,
-                  O + (size_t)n * block_m * d, LSE + (size_t)n * block_m, NULL, NULL, NULL, NULL, cn, NULL);
+        one_block_variant(&p, 0, 0.0, 0, tau, blocks[3 * n], blocks[3 * n + 1], blocks[3 * n + 2],
+                          O + (size_t)n * block_m * d, LSE + (size_t)n * block_m, NULL, NULL, cn);
     }
     return 0;
 }
@@ -565,16 +633,15 @@ int oracle_blasst_variant(const float *Q, const float *K, const float *V, int B,
     if (Hq % Hkv != 0 || block_m <= 0 || block_n <= 0 || !(ln_lambda < 0.0)) return -1;
     if (rowskip && lazy_tau >= 0.0) return -1;
     prob_t p = {Q, K, V, B, Hq, Hkv, N, d, block_m, block_n, causal, scale};
-    opts_t o = {0, 0, 0, 0, 0, 1, ln_lambda, lazy_tau, rowskip};
     const int Tc = ceil_div(N, block_n);
 #pragma omp parallel for schedule(dynamic, 1)
     for (int n = 0; n < nblk; ++n) {
         int64_t *cn = counters + (size_t)n * 4;
         cn[0] = cn[1] = cn[2] = cn[3] = 0;
-        one_block(&p, &o, NULL, blocks[3 * n], blocks[3 * n + 1], blocks[3 * n + 2], NULL,
-                  O + (size_t)n * block_m * d, LSE + (size_t)n * block_m, NULL, NULL,
-                  mask_out ? mask_out + (size_t)n * Tc : NULL,
-                  margin_out ? margin_out + (size_t)n * Tc : NULL, cn, NULL);
+        one_block_variant(&p, 1, ln_lambda, rowskip, lazy_tau, blocks[3 * n], blocks[3 * n + 1], blocks[3 * n + 2],
+                          O + (size_t)n * block_m * d, LSE + (size_t)n * block_m,
+                          mask_out ? mask_out + (size_t)n * Tc : NULL,
+                          margin_out ? margin_out + (size_t)n * Tc : NULL, cn);
     }
     return 0;
 }
