@@ -65,7 +65,8 @@ def time_sustained(fn, seconds=1.0, chunk=20):
 def ceilings(torch, dev, seed):
     """The probe library (bench_probes.hip, a library of its own): MFMAs on register operands, two waves per SIMD as in
     the attention kernels (bf16 32x32x16 and E4M3 32x32x64), once on normally distributed operands and once on zeros
-    (the clock the chip grants follows how many operand bits toggle), and a streaming read of 512 MiB."""
+    (the clock the chip grants follows how many operand bits toggle), and a streaming read of 512 MiB (as the decode
+    step, re-read every launch: the part of it that the 256 MiB memory-side cache still holds does not come from HBM)."""
     path = os.path.join(ROOT, "bench_probes.so")
     if not os.path.exists(path):
         raise RuntimeError(f"{path} is missing: build it with `python -m paper_2604_12798_amd.build`")
@@ -79,7 +80,7 @@ def ceilings(torch, dev, seed):
         f.restype = ci
         f.argtypes = [vp, vp, ci, ci, vp]
     P.hbm_read_probe_launch.restype = ci
-    P.hbm_read_probe_launch.argtypes = [vp, vp, ctypes.c_size_t, ci, vp]
+    P.hbm_read_probe_launch.argtypes = [vp, vp, ctypes.c_size_t, ci, ci, vp]
     g = torch.Generator(device="cpu").manual_seed(seed)
     blocks = torch.cuda.get_device_properties(0).multi_processor_count
     outb = torch.empty(blocks * 512, dtype=torch.float32, device=dev)
@@ -106,9 +107,9 @@ def ceilings(torch, dev, seed):
         res["fp8_" + what] = 4.0 * float(P.mfma_probe_flop(blocks, iters // 2)) / ms / 1e9
     nbytes = 512 << 20
     buf = torch.empty(nbytes, dtype=torch.uint8, device=dev).random_(generator=None)
-    rblocks = blocks * 8
+    rblocks = blocks * 2   # two 256-thread workgroups per CU, four 16-byte loads in flight per lane: the fastest of a sweep
     outr = torch.empty(rblocks * 256, dtype=torch.int32, device=dev)
-    ms = timed(lambda: P.hbm_read_probe_launch(vp(buf.data_ptr()), vp(outr.data_ptr()), nbytes, rblocks, stream()))
+    ms = timed(lambda: P.hbm_read_probe_launch(vp(buf.data_ptr()), vp(outr.data_ptr()), nbytes, rblocks, 4, stream()))
     res["hbm_read_GB/s"] = nbytes / ms / 1e6
     return res
 

@@ -67,16 +67,17 @@ __global__ __launch_bounds__(512, 2) void mfma_fp8_probe_kernel(const uint8_t* d
 
 // streaming read: every lane reads 16 bytes per step, a workgroup 4 KiB, the grid walks the buffer once
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+template <int U>
 __global__ __launch_bounds__(256) void hbm_read_probe_kernel(const u32x4* data, uint32_t* out, size_t n16) {
     const size_t stride = (size_t)gridDim.x * 256;
     u32x4 acc = {0, 0, 0, 0};
     size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    for (; i + 7 * stride < n16; i += 8 * stride) {  // eight loads in flight per lane
-        u32x4 x[8];
+    for (; i + (U - 1) * stride < n16; i += U * stride) {  // U loads in flight per lane
+        u32x4 x[U];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) x[u] = data[i + u * stride];
+        for (int u = 0; u < U; ++u) x[u] = __builtin_nontemporal_load(data + i + u * stride);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) acc ^= x[u];
+        for (int u = 0; u < U; ++u) acc ^= x[u];
     }
     for (; i < n16; i += stride) acc ^= data[i];
     out[(size_t)blockIdx.x * 256 + threadIdx.x] = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
@@ -107,11 +108,15 @@ int mfma_fp8_probe_launch(const void* data, void* out, int blocks, int iters, vo
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-// reads `bytes` (a multiple of 16) from data once; out: blocks * 256 dwords
-int hbm_read_probe_launch(const void* data, void* out, size_t bytes, int blocks, void* stream) {
+// reads `bytes` (a multiple of 16) from data once with 4, 8 or 16 loads in flight per lane; out: blocks * 256 dwords
+int hbm_read_probe_launch(const void* data, void* out, size_t bytes, int blocks, int loads_in_flight, void* stream) {
     if (!data || !out || blocks <= 0 || (bytes & 15)) return -1;
     (void)hipGetLastError();
-    hbm_read_probe_kernel<<<dim3((unsigned)blocks), 256, 0, (hipStream_t)stream>>>((const u32x4*)data, (uint32_t*)out, bytes / 16);
+    const dim3 grid((unsigned)blocks);
+    hipStream_t s = (hipStream_t)stream;
+    if (loads_in_flight >= 16) hbm_read_probe_kernel<16><<<grid, 256, 0, s>>>((const u32x4*)data, (uint32_t*)out, bytes / 16);
+    else if (loads_in_flight >= 8) hbm_read_probe_kernel<8><<<grid, 256, 0, s>>>((const u32x4*)data, (uint32_t*)out, bytes / 16);
+    else hbm_read_probe_kernel<4><<<grid, 256, 0, s>>>((const u32x4*)data, (uint32_t*)out, bytes / 16);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
