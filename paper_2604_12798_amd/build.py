@@ -8,7 +8,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvfa.so")
-SOURCES = ["vfa_fwd.hip"]
+SOURCES = ["vfa_fwd.hip", "vsa_pp.hip"]
+# attn_vsa_pp_kernel sits at the register limit; with the scheduler's default register-pressure tracking the allocator
+# spills an accumulator inside its steady loops, with this tracker it does not (checked on the generated code)
+EXTRA_FLAGS = {"vsa_pp.hip": ["-mllvm", "-amdgpu-use-amdgpu-trackers=1"]}
 
 HIPCC_FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
@@ -35,8 +38,18 @@ def _run(cmd: list[str], verbose: bool) -> None:
 
 
 def build_lib(verbose: bool = False, extra: list[str] | None = None) -> str:
+    """One object per source (some carry flags of their own), then one link."""
+    import tempfile
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    _run([hipcc] + HIPCC_FLAGS + (extra or []) + ["-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES], verbose)
+    compile_flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    with tempfile.TemporaryDirectory(prefix="vfa_build_") as tmp:
+        objs = []
+        for src in SOURCES:
+            obj = os.path.join(tmp, src + ".o")
+            _run([hipcc] + compile_flags + EXTRA_FLAGS.get(src, []) + (extra or []) + ["-c", "-o", obj, os.path.join(CSRC, src)],
+                 verbose)
+            objs.append(obj)
+        _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs, verbose)
     return LIB
 
 

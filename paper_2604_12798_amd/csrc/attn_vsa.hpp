@@ -24,6 +24,18 @@ namespace {
 // further ahead of the matrix phases than in the dense kernels), V ring of 2.  Group 0's waves fetch the K tiles,
 // group 1's the V tiles (only of tiles that either group keeps), so each wave has one kind of load in flight and its
 // own count to wait on.
+//
+// A step (one interval of one group) exists in two forms.  The general one decides per visit whether it is an
+// exact-max one, whether its tile needs a mask or is a ragged last tile, and whether it lies inside the visit list at
+// all.  The fast one is for steps whose visits (y - 2 .. y + 5) are all "plain" - frozen max, no mask, whole tile -
+// which is nearly every step of a long sequence: those questions are answered at compile time and the scalar
+// bookkeeping per step halves.  A wave issues about one instruction per five cycles whatever its kind, so scalar
+// instructions cost as much as the others here.
+// The kernel needs 233 of the 256 vector registers in its steady loops, and whether the register allocator finds that
+// fit depends on details of the formulation and on the scheduler's pressure tracking: this file is compiled in a
+// translation unit of its own (vsa_pp.hip) with the option that makes the fast loops free of scratch accesses.  A
+// scratch reload waits for vmcnt(0), which also drains the tile prefetches, so a spill inside a steady loop costs a
+// factor, not a few percent; check the generated code after touching the step body.
 constexpr int VSA_DK = 6, VSA_DV = 2, VSA_AHEAD = 5;
 constexpr int VSA_LDS_BYTES = (VSA_DK + VSA_DV) * Tile<128>::BYTES;
 
@@ -123,14 +135,21 @@ __global__ __launch_bounds__(512, 2) void attn_vsa_pp_kernel(const Params p) {
     auto own_special = [&](int k) __attribute__((always_inline)) {
         return k < n_lead && (!pb || k < vis.n1 || ((k - vis.n1 < vis.n2b) == (grp == 1)));
     };
-    auto tile_masked = [&](int j) __attribute__((always_inline)) { return (p.causal && j * BN + BN - 1 > row0) || (j + 1) * BN > N; };
+    // first key block that needs a mask: the one holding column row0 + 1 under a causal mask, else a ragged last one
+    const int j_mask = min(p.causal ? (row0 + 1) / BN : p.Tc, N / BN);
+    auto tile_masked = [&](int j) __attribute__((always_inline)) { return j >= j_mask; };
+    // "plain" visits [n_lead, k_plain): frozen max, no mask, whole tile.  The visits behind the sink / local ones walk
+    // the remaining tiles in ascending order, so the plain ones are those of them with a tile index below j_mask
+    int k_plain;
+    {
+        int cnt = max(0, j_mask - vis.n1);                                                      // such tiles below j_mask ...
+        if (vis.n2 > 0) cnt -= max(0, min(j_mask, vis.s2 + vis.n2) - max(vis.s2, vis.n1));     // ... that are not local ones
+        k_plain = min(vis.total, n_lead + max(cnt, 0));
+    }
 
     // ---- tile loads: a wave of a group moves pieces 4 u + w4 (u = 0..3; a piece = 4 rows = 1 KiB) of its group's kind
     // of tile.  The row swizzles repeat every 16 rows, so the four pieces share one per-lane offset and differ by
     // 4 KiB in the global base and in the LDS base.
-    const int r0l = 4 * w4 + (lane >> 4), cp = lane & 15;
-    const uint32_t off_ld = grp == 0 ? (uint32_t)(r0l * T::ROWB + ((cp ^ (r0l & 15)) << 4))
-                                     : (uint32_t)(r0l * T::ROWB + ((cp ^ ((r0l & 3) << 2)) << 4));
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane(
         (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)(vsa_smem + w4 * 1024));
     auto uniform64 = [&](const uint16_t* ptr) __attribute__((always_inline)) {
@@ -140,9 +159,16 @@ __global__ __launch_bounds__(512, 2) void attn_vsa_pp_kernel(const Params p) {
         return ((uint64_t)b_hi << 32) | (uint64_t)b_lo;
     };
     // tile j of K (group 0) or V (group 1) into ring slot `slot` of that ring: this wave's four pieces
-    auto issue_tile = [&](int j, int slot) __attribute__((always_inline)) {
+    auto issue_tile = [&](int j, int slot, auto fast_c) __attribute__((always_inline)) {
+        constexpr bool FAST = decltype(fast_c)::value;
         const uint16_t* src = (grp == 0 ? Kg : Vg) + (size_t)j * BN * D;
-        if (j * BN + BN <= N) {
+        if (FAST || __builtin_expect(j * BN + BN <= N, 1)) {
+            // the per-lane offset (row 4 w4 + lane / 16 of a piece, swizzled chunk) is recomputed from the lane number
+            // at every request: eight vector instructions, against a register held for the whole kernel
+            const int ln = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+            const int r0l = 4 * w4 + (ln >> 4), cp = ln & 15;
+            const uint32_t off_ld = grp == 0 ? (uint32_t)(r0l * T::ROWB + ((cp ^ (r0l & 15)) << 4))
+                                             : (uint32_t)(r0l * T::ROWB + ((cp ^ ((r0l & 3) << 2)) << 4));
             const uint64_t g0 = uniform64(src), g1 = g0 + 4096, g2 = g0 + 8192, g3 = g0 + 12288;
             const uint32_t l0 = lds0 + ((grp == 0 ? 0 : VSA_DK) + slot) * T::BYTES, l1 = l0 + 4096, l2 = l0 + 8192, l3 = l0 + 12288;
             uint32_t m0_save;  // M0 carries the LDS base of an LDS-direct load; the compiler's own value is put back at the end
@@ -211,9 +237,10 @@ __global__ __launch_bounds__(512, 2) void attn_vsa_pp_kernel(const Params p) {
         }
     };
     // this wave's say on "skip the tile of visit k" (scores in st), with the max as it stands after visit k - 1
-    auto vote = [&](const f32x16* st, int k) __attribute__((always_inline)) {
-        const int j = vis.tile(k);
-        const float mx = tile_masked(j) ? tile_rowmax<true>(st, j * BN, limit, hh) : tile_rowmax<false>(st, 0, 0, hh);
+    auto vote = [&](const f32x16* st, int k, auto fast_c) __attribute__((always_inline)) {
+        constexpr bool FAST = decltype(fast_c)::value;
+        const int j = FAST ? 0 : vis.tile(k);
+        const float mx = !FAST && __builtin_expect(tile_masked(j), 0) ? tile_rowmax<true>(st, j * BN, limit, hh) : tile_rowmax<false>(st, 0, 0, hh);
         mt = xhalf_max(mx) * p.c;
         const bool row_keeps = (qrow < N) && (mt != -INFINITY) && !(mt < m2 - p.thr2);
         const bool wave_keeps = __builtin_amdgcn_ballot_w64(row_keeps) != 0;
@@ -228,33 +255,35 @@ __global__ __launch_bounds__(512, 2) void attn_vsa_pp_kernel(const Params p) {
         return __builtin_amdgcn_readfirstlane((mine ? 1 : 0) | ((mine | other) ? 2 : 0));
     };
     // visit k has been decided: write its mask byte, and for a kept exact-max tile adopt the new max
-    auto adopt = [&](int k, bool keep) __attribute__((always_inline)) {
+    auto adopt = [&](int k, bool keep, auto fast_c) __attribute__((always_inline)) {
+        constexpr bool FAST = decltype(fast_c)::value;
         const int j = vis.tile(k);
         if (mrow && j <= j_hi_g && (tid & 255) == 0) mrow[j] = keep ? 0 : 1;  // (a tile past j_hi_g is the other block's)
-        if (keep && own_special(k)) {
+        if (!FAST && __builtin_expect(keep && own_special(k), 0)) {
             m_bef = m2;
             m2 = fmaxf(m2, mt);
         }
     };
     // softmax of kept visit k from its score buffer into pk; l and (for an exact-max tile) the rescale of l and O
-    auto softmax = [&](f32x16* st, int k) __attribute__((always_inline)) {
-        const int j = vis.tile(k);
-        if (own_special(k)) {
+    auto softmax = [&](f32x16* st, int k, auto fast_c) __attribute__((always_inline)) {
+        constexpr bool FAST = decltype(fast_c)::value;
+        const int j = FAST ? 0 : vis.tile(k);
+        if (!FAST && __builtin_expect(own_special(k), 0)) {
             const float alpha = __builtin_amdgcn_exp2f(m_bef - (m2 == -INFINITY ? 0.f : m2));
             lsum *= alpha;
 #pragma unroll
             for (int db = 0; db < DB; ++db) ot[db] *= alpha;
         }
         float mfix = m2 == -INFINITY ? 0.f : m2;
-        if (tile_masked(j)) softmax_tile<false, true, DB>(st, pk, ot, mfix, lsum, p.c, j * BN, limit, hh);
+        if (!FAST && __builtin_expect(tile_masked(j), 0)) softmax_tile<false, true, DB>(st, pk, ot, mfix, lsum, p.c, j * BN, limit, hh);
         else softmax_tile<false, false, DB>(st, pk, ot, mfix, lsum, p.c, j * BN, limit, hh);
     };
 
     // ---- prologue: K tiles 0 and 1 are requested before the m-initialisation, which stages its summary tiles in
     // the four tiles behind them (K ring slots 2 .. 4 and the first V slot; four tiles = 256 key blocks per batch)
     if (grp == 0) {
-        issue_tile(vis.tile(0), 0);
-        if (nv > 1) issue_tile(vis.tile(1), 1);
+        issue_tile(vis.tile(0), 0, std::false_type{});
+        if (nv > 1) issue_tile(vis.tile(1), 1, std::false_type{});
     }
     if (p.use_minit) {
         const uint16_t* Rg = p.Krepr + ((size_t)(b * p.Hkv + hkv) * p.Tc) * D;
@@ -274,30 +303,31 @@ __global__ __launch_bounds__(512, 2) void attn_vsa_pp_kernel(const Params p) {
         __syncthreads();
     }
     if (grp == 0)
-        for (int k = 2; k < min(nv, VSA_AHEAD); ++k) issue_tile(vis.tile(k), k);
+        for (int k = 2; k < min(nv, VSA_AHEAD); ++k) issue_tile(vis.tile(k), k, std::false_type{});
 
     if (!p.use_minit) wait_vm0_and_sync();  // nothing has waited for K tiles 0 and 1 yet
 
     // ---- the pipeline: step y = matrix phase y, then vector phase y
     int kslot = 0;                         // K ring slot of visit y
     bool keep1 = false, keep2 = false;     // this group keeps visit y - 1 / y - 2
-    auto step = [&](int y, auto buf_c, auto grp_c) __attribute__((always_inline)) {
+    auto step = [&](int y, auto buf_c, auto grp_c, auto fast_c) __attribute__((always_inline)) {
         constexpr int BUF = decltype(buf_c)::value, GRP = decltype(grp_c)::value;
+        constexpr bool FAST = decltype(fast_c)::value;  // visits y - 2 .. y + AHEAD are all plain and inside the list
         f32x16* const st_new = BUF ? sb : sa;   // Q.K^T of visit y goes here
         f32x16* const st_old = BUF ? sa : sb;   // scores of visit y - 1
         // -- matrix phase
         if (GRP == 0) {  // interval y starts: the votes of visit y - 1 are in
             keep1 = false;
-            if (y >= 1 && y <= nv) {
+            if (FAST || (y >= 1 && y <= nv)) {
                 keep1 = (read_votes(y - 1) & 1) != 0;
-                adopt(y - 1, keep1);
+                adopt(y - 1, keep1, fast_c);
             }
         }
         __builtin_amdgcn_s_setprio(1);
-        if (y >= 2 && keep2) pv(BUF);  // V of visit y - 2 sits in slot (y - 2) & 1 = BUF
-        if (y < nv) {
+        if ((FAST || y >= 2) && keep2) pv(BUF);  // V of visit y - 2 sits in slot (y - 2) & 1 = BUF
+        if (FAST || y < nv) {
             qk(st_new, kslot);
-            vote(st_new, y);
+            vote(st_new, y, fast_c);
         }
         __builtin_amdgcn_s_setprio(0);
         __builtin_amdgcn_sched_barrier(0);
@@ -307,22 +337,22 @@ __global__ __launch_bounds__(512, 2) void attn_vsa_pp_kernel(const Params p) {
         }
         // -- vector phase
         bool keep0 = false;
-        if (GRP == 1 && y < nv) {  // interval y + 1 starts: the votes of visit y are in
+        if (GRP == 1 && (FAST || y < nv)) {  // interval y + 1 starts: the votes of visit y are in
             const int v = read_votes(y);
             keep0 = (v & 1) != 0;
-            if (v & 2) issue_tile(vis.tile(y), BUF);
+            if (v & 2) issue_tile(vis.tile(y), BUF, fast_c);
         }
         if (GRP == 0) {  // K tile of visit y + AHEAD; the tile of visit y + 1 has landed before this interval ends
-            if (y + VSA_AHEAD < nv) {
-                issue_tile(vis.tile(y + VSA_AHEAD), kslot == 0 ? VSA_DK - 1 : kslot - 1);
+            if (FAST || y + VSA_AHEAD < nv) {
+                issue_tile(vis.tile(y + VSA_AHEAD), kslot == 0 ? VSA_DK - 1 : kslot - 1, fast_c);
                 __builtin_amdgcn_s_waitcnt(0x4F70);  // vmcnt(16): all but the last four tiles' pieces
             } else {
                 __builtin_amdgcn_s_waitcnt(0x0F70);
             }
             // V of visit y - 1, if anyone keeps it, is fetched by group 1 at the start of this interval
         }
-        if (y >= 1 && y <= nv && keep1) softmax(st_old, y - 1);
-        if (GRP == 1 && y < nv) adopt(y, keep0);  // (after the softmax of visit y - 1, which still needs the max as it was)
+        if ((FAST || (y >= 1 && y <= nv)) && keep1) softmax(st_old, y - 1, fast_c);
+        if (GRP == 1 && (FAST || y < nv)) adopt(y, keep0, fast_c);  // (after the softmax of visit y - 1, which still needs the max as it was)
         __builtin_amdgcn_sched_barrier(0);
         if (GRP == 0) __builtin_amdgcn_s_barrier();
         keep2 = keep1;
@@ -331,10 +361,24 @@ __global__ __launch_bounds__(512, 2) void attn_vsa_pp_kernel(const Params p) {
     };
     auto run = [&](auto grp_c) __attribute__((always_inline)) {
         // steps 0 .. nv + 1 (the last two drain the pipeline), rounded up to an even count so that a step's score
-        // buffer is a compile-time choice; the extra step only passes its barrier
-        for (int y = 0; y < nv + 2; y += 2) {
-            step(y, std::integral_constant<int, 0>{}, grp_c);
-            step(y + 1, std::integral_constant<int, 1>{}, grp_c);
+        // buffer is a compile-time choice; the extra step only passes its barrier.  General steps up to the first step
+        // whose visits are all plain, fast steps (in pairs) while they stay plain, general steps for the rest
+        int y = 0;
+        const int y_f0 = (n_lead + 2 + 1) & ~1;  // y - 2 >= n_lead, rounded up to even
+        const int y_f1 = k_plain - VSA_AHEAD;    // y + AHEAD < k_plain; fast steps are y_f0 <= y < y_f1
+        if (y_f0 + 2 <= y_f1) {
+            for (; y < y_f0; y += 2) {
+                step(y, std::integral_constant<int, 0>{}, grp_c, std::false_type{});
+                step(y + 1, std::integral_constant<int, 1>{}, grp_c, std::false_type{});
+            }
+            for (; y + 2 <= y_f1; y += 2) {
+                step(y, std::integral_constant<int, 0>{}, grp_c, std::true_type{});
+                step(y + 1, std::integral_constant<int, 1>{}, grp_c, std::true_type{});
+            }
+        }
+        for (; y < nv + 2; y += 2) {
+            step(y, std::integral_constant<int, 0>{}, grp_c, std::false_type{});
+            step(y + 1, std::integral_constant<int, 1>{}, grp_c, std::false_type{});
         }
         store_output<D>(p, ot, m2, lsum, b, h, qrow, hh);
     };

@@ -1,5 +1,5 @@
 // C ABI of libvfa.so (declared in vfa.h): argument checks, kernel selection and launches.  The kernels live in the
-// headers included below; everything is compiled for gfx950 in this one translation unit.
+// headers included below and are compiled for gfx950 in this translation unit, except attn_vsa_pp_kernel (vsa_pp.hip).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <math.h>
@@ -10,7 +10,7 @@
 #include "common.hpp"
 #include "attn_generic.hpp"
 #include "attn_pingpong.hpp"
-#include "attn_vsa.hpp"
+#include "vsa_pp.hpp"
 #include "summary.hpp"
 #include "decode.hpp"
 #include "fp8.hpp"
@@ -87,7 +87,12 @@ int launch_fwd(const Params& p, int d, int block_m, hipStream_t s) {
         (head_pairs || MODE != MODE_VSA || (p.causal && p.n_local <= 1))) {
         static std::atomic<unsigned char> lds_raised[kMaxDevices];  // one set of flags per instantiation
         if constexpr (MODE == MODE_VSA) {
-            if (!raise_lds_limit(&attn_vsa_pp_kernel, VSA_LDS_BYTES, lds_raised)) return VFA_ERR_HIP;
+            const int dev = current_device();
+            if (dev < 0) return VFA_ERR_HIP;
+            if (!lds_raised[dev].load(std::memory_order_acquire)) {
+                if (vfa_detail_vsa_pp_raise_lds() != 0) return VFA_ERR_HIP;
+                lds_raised[dev].store(1, std::memory_order_release);
+            }
         } else {
             if (!raise_lds_limit(&attn_fwd_pp_kernel<MODE>, PP_LDS_BYTES, lds_raised)) return VFA_ERR_HIP;
         }
@@ -103,8 +108,8 @@ int launch_fwd(const Params& p, int d, int block_m, hipStream_t s) {
             n_wg = (unsigned)n_cu;
         }
         const dim3 grid_pp(n_wg);
-        if constexpr (MODE == MODE_VSA) attn_vsa_pp_kernel<<<grid_pp, 512, VSA_LDS_BYTES, s>>>(q);
-        else attn_fwd_pp_kernel<MODE><<<grid_pp, 512, PP_LDS_BYTES, s>>>(q);
+        if constexpr (MODE == MODE_VSA) return vfa_detail_vsa_pp_launch(&q, sizeof(q), n_wg, s) == 0 ? VFA_OK : VFA_ERR_HIP;
+        attn_fwd_pp_kernel<MODE><<<grid_pp, 512, PP_LDS_BYTES, s>>>(q);
         return hipGetLastError() == hipSuccess ? VFA_OK : VFA_ERR_HIP;
     }
     const dim3 grid((unsigned)(p.B * p.Hq * p.Tr));
