@@ -146,6 +146,48 @@ def test_vsa_mask_bit_exact_and_output(vfa, oracle, name, w, thr):
     assert sparsity > 0.02
 
 
+# The VSA ping-pong kernel runs a step in a general or in a fast form, chosen per step from the visit list's shape
+# (sink / local visits at the head, masked or ragged tiles at the tail, five visits of look-ahead).  Non-causal lengths
+# put the same visit count on every query block, so a sweep over lengths walks the switch points one by one: no fast
+# step at all, a single pair, a ragged last tile that shortens the fast range, sinks / locals that move its start.
+STEP_FORM_CASES = [
+    ("pairs_tc9", W(B=1, Hq=4, Hkv=2, N=576, beta=6.0, kappa=3.0, causal=False), 5.0),
+    ("pairs_tc11", W(B=1, Hq=4, Hkv=2, N=704, beta=6.0, kappa=3.0, causal=False), 5.0),
+    ("pairs_tc13_ragged", W(B=1, Hq=4, Hkv=2, N=801, beta=6.0, kappa=3.0, causal=False), 5.0),
+    ("pairs_tc14", W(B=1, Hq=4, Hkv=2, N=896, beta=6.0, kappa=3.0, causal=False), 9.0),
+    ("pairs_tc19_sink2", W(B=1, Hq=4, Hkv=2, N=1216, beta=6.0, kappa=3.0, causal=False, n_sink=2), 5.0),
+    ("blocks_tc12", W(B=1, Hq=2, Hkv=2, N=768, beta=6.0, kappa=3.0, causal=False), 9.0),
+    ("blocks_tc15_ragged", W(B=1, Hq=2, Hkv=2, N=930, beta=6.0, kappa=3.0, causal=False), 5.0),
+    ("blocks_tc20_causal_ragged", W(B=1, Hq=2, Hkv=2, N=1250, beta=6.0, kappa=3.0), 4.0),
+    ("pairs_tc24_causal_no_sink", W(B=1, Hq=4, Hkv=2, N=1536, beta=6.0, kappa=3.0, n_sink=0), 4.0),
+]
+
+
+@pytest.mark.parametrize("name,w,thr", STEP_FORM_CASES, ids=[c[0] for c in STEP_FORM_CASES])
+def test_vsa_step_forms_switch_points(vfa, oracle, name, w, thr):
+    import torch
+    t = wl.generate(w)
+    Q, K, V = gpu_inputs(t)
+    Qh, Kh, Vh = host_f32(t)
+    blocks = wl.all_blocks(w)
+    O, L, M = vfa.vsa_attn_fwd(Q, K, V, block_m=w.block_m, block_n=w.block_n, causal=w.causal, n_sink=w.n_sink,
+                               n_local=w.n_local, skip_threshold_nats=thr)
+    torch.cuda.synchronize()
+    ref = oracle.blocks(Qh, Kh, Vh, w.block_m, w.block_n, w.causal, blocks, n_sink=w.n_sink, n_local=w.n_local,
+                        vsa=True, skip_threshold_nats=thr)
+    got = M.cpu().numpy().reshape(len(blocks), w.Tc)
+    near = np.abs(ref["margin"]) < MASK_GUARD_NATS
+    assert near.sum() <= 2, "too many tiles sit on the threshold"
+    assert np.array_equal(got[~near], ref["mask"][~near]), (name, int((got[~near] != ref["mask"][~near]).sum()))
+    clean = ~near.any(axis=1)
+    stats = check_o_lse(O, L, ref["O"][clean], ref["LSE"][clean], np.asarray(blocks)[clean], w.block_m, w.N,
+                        "vsa_attn_fwd vs oracle VSA")
+    kept = (ref["mask"] == 0).sum()
+    skipped = (ref["mask"] == 1).sum()
+    print(name, "kept %d skipped %d" % (kept, skipped), stats, flush=True)
+    assert kept > 0 and skipped > 0, "the case should mix kept and skipped tiles"
+
+
 def test_vsa_huge_threshold_equals_vfa(vfa):
     """With a threshold nothing reaches Alg. 2 is Alg. 1.  The two kernels add a tile's row sum into l in a
     different order (Alg. 2 commits each tile's sum as one number once the block's decision is known), so
