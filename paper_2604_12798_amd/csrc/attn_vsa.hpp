@@ -147,6 +147,11 @@ __global__ __launch_bounds__(512, 2) void attn_vsa_pp_kernel(const Params p) {
         k_plain = min(vis.total, n_lead + max(cnt, 0));
     }
 
+    // vis.tile(k) for a visit behind the sink / local ones (k >= n_lead): the remaining tiles in ascending order
+    auto tile_plain = [&](int k) __attribute__((always_inline)) {
+        const int t = k - vis.n2;
+        return (vis.n2 > 0 && t >= vis.s2) ? t + vis.n2 : t;
+    };
     // ---- tile loads: a wave of a group moves pieces 4 u + w4 (u = 0..3; a piece = 4 rows = 1 KiB) of its group's kind
     // of tile.  The row swizzles repeat every 16 rows, so the four pieces share one per-lane offset and differ by
     // 4 KiB in the global base and in the LDS base.
@@ -257,7 +262,7 @@ __global__ __launch_bounds__(512, 2) void attn_vsa_pp_kernel(const Params p) {
     // visit k has been decided: write its mask byte, and for a kept exact-max tile adopt the new max
     auto adopt = [&](int k, bool keep, auto fast_c) __attribute__((always_inline)) {
         constexpr bool FAST = decltype(fast_c)::value;
-        const int j = vis.tile(k);
+        const int j = FAST ? tile_plain(k) : vis.tile(k);
         if (mrow && j <= j_hi_g && (tid & 255) == 0) mrow[j] = keep ? 0 : 1;  // (a tile past j_hi_g is the other block's)
         if (!FAST && __builtin_expect(keep && own_special(k), 0)) {
             m_bef = m2;
@@ -323,6 +328,7 @@ __global__ __launch_bounds__(512, 2) void attn_vsa_pp_kernel(const Params p) {
                 adopt(y - 1, keep1, fast_c);
             }
         }
+        __builtin_amdgcn_sched_barrier(0);  // (the decision's bookkeeping stays in front of the matrix phase)
         __builtin_amdgcn_s_setprio(1);
         if ((FAST || y >= 2) && keep2) pv(BUF);  // V of visit y - 2 sits in slot (y - 2) & 1 = BUF
         if (FAST || y < nv) {
@@ -340,11 +346,11 @@ __global__ __launch_bounds__(512, 2) void attn_vsa_pp_kernel(const Params p) {
         if (GRP == 1 && (FAST || y < nv)) {  // interval y + 1 starts: the votes of visit y are in
             const int v = read_votes(y);
             keep0 = (v & 1) != 0;
-            if (v & 2) issue_tile(vis.tile(y), BUF, fast_c);
+            if (v & 2) issue_tile(FAST ? tile_plain(y) : vis.tile(y), BUF, fast_c);
         }
         if (GRP == 0) {  // K tile of visit y + AHEAD; the tile of visit y + 1 has landed before this interval ends
             if (FAST || y + VSA_AHEAD < nv) {
-                issue_tile(vis.tile(y + VSA_AHEAD), kslot == 0 ? VSA_DK - 1 : kslot - 1, fast_c);
+                issue_tile(FAST ? tile_plain(y + VSA_AHEAD) : vis.tile(y + VSA_AHEAD), kslot == 0 ? VSA_DK - 1 : kslot - 1, fast_c);
                 __builtin_amdgcn_s_waitcnt(0x4F70);  // vmcnt(16): all but the last four tiles' pieces
             } else {
                 __builtin_amdgcn_s_waitcnt(0x0F70);
