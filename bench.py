@@ -144,6 +144,27 @@ def max_gap(w: wl.Workload, t: dict, n_random: int):
             "rows": int(ok.sum()), "blocks": int(len(blocks))}
 
 
+def stabilisation_stats(w: wl.Workload, t: dict, n_random: int):
+    """Where the online-softmax running maximum reaches its final value (the paper's stabilisation position j*), from
+    the float64 oracle on a sample of query blocks: share of rows that stabilise in a sink block, in a local block
+    (the blocks Alg. 1 visits first), or elsewhere."""
+    import oracle
+    Q, K, V = (wl.bf16_bits_to_f32(t[k]) for k in "QKV")
+    blocks = wl.sample_blocks(w, n_random)
+    js = oracle.stabilisation_index(Q, K, V, w.block_m, w.block_n, w.causal, blocks)
+    sink = local = other = 0
+    for a, (_, _, i) in enumerate(blocks):
+        r0, r1 = i * w.block_m, min(w.N, (i + 1) * w.block_m) - 1
+        lo = max(0, r0 // w.block_n - (w.n_local - 1)) if w.n_local > 0 else 1 << 30
+        hi = r1 // w.block_n if w.n_local > 0 else -1
+        j = js[a][js[a] >= 0]
+        is_sink = j < w.n_sink
+        is_local = (~is_sink) & (j >= lo) & (j <= hi)
+        sink += int(is_sink.sum()); local += int(is_local.sum()); other += int((~is_sink & ~is_local).sum())
+    rows = sink + local + other
+    return {"rows": rows, "frac_sink": sink / rows, "frac_local": local / rows, "frac_elsewhere": other / rows}
+
+
 def time_region(fn, steps, warmup):
     """ms per call, timed with HIP events on the stream fn launches on (torch's current stream)."""
     import torch
@@ -433,6 +454,7 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, t, args.cpu_sample)
         out["frozen_max_gap_nats"] = max_gap(w, t, 24)   # oracle diagnostic on a small sample of query blocks
+        out["running_max_stabilisation"] = stabilisation_stats(w, t, 24)
     print(json.dumps(out), flush=True)
 
 

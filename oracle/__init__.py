@@ -258,3 +258,19 @@ def fa2(Q, K, V, block_m, block_n, causal, blocks_, scale=None, want_traj=False)
     """FA column of Table 1: ascending order, exact-max update on every block."""
     return blocks(Q, K, V, block_m, block_n, causal, blocks_, n_sink=0, n_local=0, use_minit=False,
                   reorder=False, freeze=False, scale=scale, want_traj=want_traj)
+
+
+def stabilisation_index(Q, K, V, block_m, block_n, causal, blocks_, scale=None):
+    """Where the running maximum stabilises (attention-statistics section, the stabilisation-position equation): for
+    every row of the listed query blocks, the first key block j of the default ascending scan at which the
+    online-softmax running maximum m^(j) equals its final value m^(T_c).  Taken from the trajectory of the FA column
+    of Table 1 (fa2), block by block, as the equation reads.  Returns int64 [n, block_m]; -1 for rows past the end of
+    the sequence."""
+    r = fa2(Q, K, V, block_m, block_n, causal, blocks_, scale=scale, want_traj=True)
+    m = r["traj"][..., 0]                       # [n, Tc, block_m]: m after the k-th block (NaN: block not visited)
+    final = r["m_final"]                        # [n, block_m]
+    n, Tc, Br = m.shape
+    hit = m == final[:, None, :]                # NaN compares unequal: unvisited blocks and absent rows never hit
+    first = np.argmax(hit, axis=1)              # index of the first block that hits (0 where none does)
+    return np.where(hit.any(axis=1), first, -1).astype(np.int64)
+

@@ -822,3 +822,49 @@ def test_bf16_rounding_is_nearest_even():
     y = np.random.default_rng(0).standard_normal(10000).astype(np.float32) * 37
     t = torch.from_numpy(y).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
     assert np.array_equal(wl.f32_to_bf16_bits(y), t)
+
+
+# ---- where the running maximum stabilises (attention-statistics section, stabilisation-position equation)
+def test_stabilisation_index_is_the_block_of_a_planted_maximum(oracle):
+    """One key per row made the unique largest score by construction: j* is that key's block, for every row."""
+    rng = np.random.default_rng(7)
+    N, d, bm, bn = 320, 16, 64, 32
+    Q = rng.standard_normal((1, 1, N, d)).astype(np.float32)
+    K = (0.01 * rng.standard_normal((1, 1, N, d))).astype(np.float32)
+    V = rng.standard_normal((1, 1, N, d)).astype(np.float32)
+    planted = 5 * bn + 3                      # key 163, block 5
+    K[0, 0, planted] = 0.0
+    Q[..., 0] = 4.0                           # every query has a large first coordinate ...
+    K[0, 0, planted, 0] = 8.0                 # ... and only the planted key answers it
+    blocks = np.array([[0, 0, i] for i in range(N // bm)], dtype=np.int32)
+    js = oracle.stabilisation_index(Q, K, V, bm, bn, False, blocks)
+    assert js.shape == (N // bm, bm) and np.all(js == 5)
+    # causal: rows before the planted key cannot see it; rows from the planted key on stabilise in its block
+    jc = oracle.stabilisation_index(Q, K, V, bm, bn, True, blocks)
+    rows = np.arange(N).reshape(N // bm, bm)
+    assert np.all(jc[rows >= planted] == 5)
+    assert np.all(jc[rows < planted] <= rows[rows < planted] // bn)
+
+
+def test_stabilisation_index_against_brute_force_argmax(oracle):
+    """The running maximum reaches its final value in the block that holds the first occurrence of the row's largest
+    score: brute force over a full score matrix, ragged length, causal and not."""
+    rng = np.random.default_rng(11)
+    N, d, bm, bn = 150, 8, 32, 16
+    Q = rng.standard_normal((1, 2, N, d)).astype(np.float32)
+    K = rng.standard_normal((1, 1, N, d)).astype(np.float32)
+    V = rng.standard_normal((1, 1, N, d)).astype(np.float32)
+    Tr = -(-N // bm)
+    blocks = np.array([[0, h, i] for h in range(2) for i in range(Tr)], dtype=np.int32)
+    for causal in (False, True):
+        js = oracle.stabilisation_index(Q, K, V, bm, bn, causal, blocks)
+        for a, (_, h, i) in enumerate(blocks):
+            for rr in range(bm):
+                row = i * bm + rr
+                if row >= N:
+                    assert js[a, rr] == -1
+                    continue
+                s = Q[0, h, row].astype(np.float64) @ K[0, 0].astype(np.float64).T
+                if causal:
+                    s = s[: row + 1]
+                assert js[a, rr] == int(np.argmax(s)) // bn
