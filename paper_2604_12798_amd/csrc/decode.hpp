@@ -14,8 +14,8 @@ namespace {
 //                        sum exp(s - m) and sum exp(s - m) v over the split's key range
 //   decode_merge_kernel  per query head: ADD the partial sums (no max in the merge, because no split
 //                        ever rescales), divide, write O and LSE
-// The work is HBM bound (K and V are read once), so single-wave workgroups with a two-deep tile ring
-// (64 KiB of LDS, two per CU) and the same tile helpers as the prefill kernels are enough.
+// The work is HBM bound (K and V are read once), so single-wave workgroups with a small tile ring (64 KiB of LDS, two
+// per CU) and the same tile helpers as the prefill kernels are enough.
 struct DecodeParams {
     const uint16_t* Q;      // [B, Hq, d]
     const uint16_t* K;      // [B, Hkv, n_cap, d]
@@ -83,13 +83,14 @@ template <int D>
 __global__ __launch_bounds__(64) void decode_split_kernel(const DecodeParams p) {
     using T = Tile<D>;
     constexpr int DB = D / 32;
-    // K is double buffered, V single buffered: 3 tiles = 48 KiB at d = 128, so three workgroups share a CU
-    // and keep three times (next K tile + this V tile) in flight, which is what an HBM-bound loop needs
-    __shared__ __attribute__((aligned(16))) uint8_t smem[3 * T::BYTES];
+    // K ring of three tiles filled two tiles ahead, V single buffered: 4 tiles = 64 KiB at d = 128, two workgroups per
+    // CU; no wait in the loop drains the load queue: each waits only for the tile it is about to read
+    __shared__ __attribute__((aligned(16))) uint8_t smem[4 * T::BYTES];
     uint8_t* const Ks = smem;
-    uint8_t* const Vs = smem + 2 * T::BYTES;
+    uint8_t* const Vs = smem + 3 * T::BYTES;
     constexpr int NI = BN / (1024 / T::ROWB);  // load instructions per tile (one wave)
-    constexpr int WAIT_ALL_BUT_ONE_TILE = 0x0F70 | (NI & 15) | ((NI >> 4) << 14);  // s_waitcnt vmcnt(NI)
+    constexpr int WAIT_BUT_1 = 0x0F70 | (NI & 15) | ((NI >> 4) << 14);              // s_waitcnt vmcnt(NI)
+    constexpr int WAIT_BUT_2 = 0x0F70 | ((2 * NI) & 15) | (((2 * NI) >> 4) << 14);  // s_waitcnt vmcnt(2 NI)
     const int lane = threadIdx.x, ql = lane & 31, hh = lane >> 5;
     const int split = blockIdx.x, bh = blockIdx.y;
     int b, h;
@@ -109,25 +110,33 @@ __global__ __launch_bounds__(64) void decode_split_kernel(const DecodeParams p) 
 #pragma unroll
     for (int db = 0; db < DB; ++db) ot[db] = f32x16{0};
     float lsum = 0.f;
-    if (t_lo < t_hi) {
-        load_tile<D, 1>(Kg, t_lo * BN, n_keys, Ks, false, 0, lane);
-        wait_vm0_and_sync();
-    }
+    // requests in flight, oldest first, at the top of iteration t: K(t) [first iteration only], K(t + 1)
+    if (t_lo < t_hi) load_tile<D, 1>(Kg, t_lo * BN, n_keys, Ks, false, 0, lane);
+    if (t_lo + 1 < t_hi) load_tile<D, 1>(Kg, (t_lo + 1) * BN, n_keys, Ks + T::BYTES, false, 0, lane);
+    int slot = 0;
     for (int t = t_lo; t < t_hi; ++t) {
-        const int cur = (t - t_lo) & 1;
         // the V buffer's last readers (the P.V MFMAs of the previous tile) have all issued
         load_tile<D, 1>(Vg, t * BN, n_keys, Vs, true, 0, lane);
-        const bool more = t + 1 < t_hi;
-        if (more) load_tile<D, 1>(Kg, (t + 1) * BN, n_keys, Ks + (cur ^ 1) * T::BYTES, false, 0, lane);
+        const int s2 = slot >= 1 ? slot - 1 : 2;  // slot of K(t + 2) = (slot + 2) % 3
+        const bool more2 = t + 2 < t_hi, more1 = t + 1 < t_hi;
+        if (more2) load_tile<D, 1>(Kg, (t + 2) * BN, n_keys, Ks + s2 * T::BYTES, false, 0, lane);
+        // K(t) has landed when at most [K(t + 1)], V(t), [K(t + 2)] are still out
+        const int later = (more1 ? 1 : 0) + 1 + (more2 ? 1 : 0);
+        if (later == 3) __builtin_amdgcn_s_waitcnt(0x0F70 | ((3 * NI) & 15) | (((3 * NI) >> 4) << 14));
+        else if (later == 2) __builtin_amdgcn_s_waitcnt(WAIT_BUT_2);
+        else __builtin_amdgcn_s_waitcnt(WAIT_BUT_1);
+        __syncthreads();
         f32x16 st[2];
         uint32_t pk[16];
-        qk_tile_pipe<D>(Ks + cur * T::BYTES, qf, st, ql, hh);
+        qk_tile_pipe<D>(Ks + slot * T::BYTES, qf, st, ql, hh);
         softmax_tile<false, true, DB>(st, pk, ot, m2, lsum, p.c, t * BN, n_keys - 1, hh);  // frozen max, ragged tail masked
-        if (more) __builtin_amdgcn_s_waitcnt(WAIT_ALL_BUT_ONE_TILE);  // V(t) has landed; K(t + 1) may still be on its way
+        // V(t) has landed when at most K(t + 2) is still out (K(t + 1) was requested before V(t))
+        if (more2) __builtin_amdgcn_s_waitcnt(WAIT_BUT_1);
         else __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
         pv_tile_pipe<D>(Vs, pk, ot, lane, hh);
-        wait_vm0_and_sync();
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this tile's LDS reads are done before its buffers are refilled
+        slot = slot == 2 ? 0 : slot + 1;
     }
     const float l = xhalf_sum(lsum);
     if (ql < p.Hq / p.Hkv) {
