@@ -166,7 +166,11 @@ __device__ __forceinline__ void pv_tile8(const uint8_t* vt, const uint32_t* pk, 
 // mantissa bit for 14 more binades below 1: for a frozen max that may sit far above the scores
 template <bool P_BF8>
 __device__ __forceinline__ uint32_t pack_p8(const float* q) {
-    s16x2 w = {0, 0};
+    // each conversion writes one half of w and keeps the other: start from whatever the register holds (an empty
+    // asm "defines" it) instead of spending a move per dword on a zero that the second conversion overwrites
+    uint32_t w0;
+    asm volatile("" : "=v"(w0));
+    s16x2 w = __builtin_bit_cast(s16x2, w0);
     if (P_BF8) {
         w = __builtin_amdgcn_cvt_scalef32_pk_bf8_f32(w, q[0], q[1], 0x1p-15f, false);
         w = __builtin_amdgcn_cvt_scalef32_pk_bf8_f32(w, q[2], q[3], 0x1p-15f, true);
