@@ -188,6 +188,56 @@ def test_vsa_step_forms_switch_points(vfa, oracle, name, w, thr):
     assert kept > 0 and skipped > 0, "the case should mix kept and skipped tiles"
 
 
+def _random_shapes(n, seed):
+    """Seeded shapes inside the library's domain: d, block_m, heads per KV head (even, odd, one), causal or not, 0-2 sink
+    and 0-3 local blocks, lengths from a fraction of a tile to about 30 tiles, mostly ragged."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        d = int(rng.choice([64, 128], p=[0.3, 0.7]))
+        g = int(rng.choice([1, 2, 3, 4]))
+        Hkv = int(rng.choice([1, 2]))
+        kw = dict(B=int(rng.choice([1, 2])), Hq=g * Hkv, Hkv=Hkv, N=int(rng.integers(40, 2000)), d=d,
+                  block_m=int(rng.choice([64, 128], p=[0.3, 0.7])), causal=bool(rng.integers(0, 2)),
+                  n_sink=int(rng.integers(0, 3)), n_local=int(rng.integers(0, 4)), beta=6.0, kappa=3.0)
+        if kw["n_sink"] + kw["n_local"] == 0:
+            kw["n_sink"] = 1
+        if d == 64:
+            kw["F"] = 4
+        name = "r%d_d%d_bm%d_g%d_N%d_%s_s%dl%d" % (i, d, kw["block_m"], g, kw["N"], "c" if kw["causal"] else "nc",
+                                                   kw["n_sink"], kw["n_local"])
+        out.append((name, W(**kw), float(rng.choice([3.0, 4.0, 6.0]))))
+    return out
+
+
+RANDOM_SHAPES = _random_shapes(20, 20260412)
+
+
+@pytest.mark.parametrize("name,w,thr", RANDOM_SHAPES, ids=[c[0] for c in RANDOM_SHAPES])
+def test_random_shapes(vfa, oracle, name, w, thr):
+    """Every forward entry point on shapes nobody picked by hand: the dense paths against exact attention and their own
+    recurrences, Alg. 2 with the mask compared outside the guard band around the threshold."""
+    import torch
+    t = wl.generate(w)
+    blocks = wl.all_blocks(w)
+    print(name, _run_all(vfa, w, t, blocks, oracle), flush=True)
+    Q, K, V = gpu_inputs(t)
+    Qh, Kh, Vh = host_f32(t)
+    O, L, M = vfa.vsa_attn_fwd(Q, K, V, block_m=w.block_m, block_n=w.block_n, causal=w.causal, n_sink=w.n_sink,
+                               n_local=w.n_local, skip_threshold_nats=thr)
+    torch.cuda.synchronize()
+    ref = oracle.blocks(Qh, Kh, Vh, w.block_m, w.block_n, w.causal, blocks, n_sink=w.n_sink, n_local=w.n_local,
+                        vsa=True, skip_threshold_nats=thr)
+    got = M.cpu().numpy().reshape(len(blocks), w.Tc)
+    near = np.abs(ref["margin"]) < MASK_GUARD_NATS
+    assert near.sum() <= 2, "too many tiles sit on the threshold"
+    assert np.array_equal(got[~near], ref["mask"][~near]), (name, int((got[~near] != ref["mask"][~near]).sum()))
+    clean = ~near.any(axis=1)
+    stats = check_o_lse(O, L, ref["O"][clean], ref["LSE"][clean], np.asarray(blocks)[clean], w.block_m, w.N,
+                        "vsa_attn_fwd vs oracle VSA")
+    print(name, "vsa kept %d skipped %d" % ((ref["mask"] == 0).sum(), (ref["mask"] == 1).sum()), stats, flush=True)
+
+
 def test_vsa_huge_threshold_equals_vfa(vfa):
     """With a threshold nothing reaches Alg. 2 is Alg. 1.  The two kernels add a tile's row sum into l in a
     different order (Alg. 2 commits each tile's sum as one number once the block's decision is known), so
