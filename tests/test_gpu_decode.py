@@ -62,6 +62,39 @@ def test_decode_matches_oracle(vfa, oracle, name, shape, n_keys, kw):
     print(name, stats, flush=True)
 
 
+def _random_decode_cases(n, seed):
+    """Seeded decode shapes: heads per KV head from 1 to 32, d, cache capacity and fill, 1 to 24 key ranges (also more
+    ranges than tiles), 0-2 sink and 0-3 local blocks, with and without the summary estimate."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        d = int(rng.choice([64, 128], p=[0.3, 0.7]))
+        g = int(rng.choice([1, 2, 3, 4, 8, 32]))
+        Hkv = int(rng.choice([1, 2])) if g < 32 else 1
+        n_cap = int(rng.choice([320, 1024, 1536, 2500]))
+        n_keys = int(rng.integers(1, n_cap + 1))
+        kw = dict(n_splits=int(rng.integers(1, 25)), n_sink=int(rng.integers(0, 3)), n_local=int(rng.integers(0, 4)))
+        if rng.integers(0, 4) == 0 and kw["n_sink"] + kw["n_local"] > 0:
+            kw["use_minit"] = False
+        shape = dict(B=int(rng.choice([1, 2, 3])), Hq=g * Hkv, Hkv=Hkv, n_cap=n_cap, d=d)
+        if d == 64:
+            shape["F"] = 4
+        name = "r%d_d%d_g%d_%dof%d_s%d_sink%d_local%d%s" % (i, d, g, n_keys, n_cap, kw["n_splits"], kw["n_sink"], kw["n_local"],
+                                                          "" if kw.get("use_minit", True) else "_noest")
+        out.append((name, shape, n_keys, kw))
+    return out
+
+
+RANDOM_CASES = _random_decode_cases(16, 20260412)
+
+
+@pytest.mark.parametrize("name,shape,n_keys,kw", RANDOM_CASES, ids=[c[0] for c in RANDOM_CASES])
+def test_decode_random_shapes(vfa, oracle, name, shape, n_keys, kw):
+    t = _cache(**shape)
+    stats, _ = _check(vfa, oracle, t, n_keys, **kw)
+    print(name, stats, flush=True)
+
+
 def test_summary_append_equals_full_recompute(vfa, oracle):
     import torch
     t = _cache(B=2, Hq=2, Hkv=2, n_cap=1024, d=128)
