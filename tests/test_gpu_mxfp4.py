@@ -84,6 +84,26 @@ SHAPES = [
 ]
 
 
+def _random_shapes(n, seed):
+    """Seeded shapes inside this path's domain (d = 128, 128 x 64 blocks): batch, heads per KV head, causal or not,
+    1-2 sink and 1-3 local blocks, lengths from a fraction of a tile to about 30 tiles, mostly ragged.  Sink and local
+    blocks are always visited: 8-bit weights are capped at 1, so a frozen max more than the headroom (2.77 nats) below
+    the true one changes the result, and on this data the summary estimate alone is up to 4.7 nats low without the exact
+    visit of the sink tile and 2.5 (E4M3 operands) to 3 nats (MXFP4) low without that of the diagonal (the capped regime
+    has its own test: finite, not NaN)."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        g, Hkv = int(rng.choice([1, 2, 3, 4])), int(rng.choice([1, 2]))
+        kw = dict(B=int(rng.choice([1, 2])), Hq=g * Hkv, Hkv=Hkv, N=int(rng.integers(30, 2000)), causal=bool(rng.integers(0, 2)),
+                  n_sink=int(rng.integers(1, 3)), n_local=int(rng.integers(1, 4)))
+        out.append(("r%d_g%d_N%d_%s_s%dl%d" % (i, g, kw["N"], "c" if kw["causal"] else "nc", kw["n_sink"], kw["n_local"]), W(**kw)))
+    return out
+
+
+RANDOM_SHAPES = _random_shapes(8, 20260412)
+
+
 @pytest.mark.parametrize("name,w", SHAPES[:3], ids=[s[0] for s in SHAPES[:3]])
 @pytest.mark.parametrize("fold", [False, True], ids=["plain", "prescaled"])
 def test_quantiser_is_byte_exact(vfa, oracle, name, w, fold):
@@ -120,7 +140,7 @@ def test_summaries_are_byte_exact(vfa, oracle, name, w):
     assert np.array_equal(oracle.mx_dequantize(want_c, want_s, 1), R)
 
 
-@pytest.mark.parametrize("name,w", SHAPES, ids=[s[0] for s in SHAPES])
+@pytest.mark.parametrize("name,w", SHAPES + RANDOM_SHAPES, ids=[s[0] for s in SHAPES + RANDOM_SHAPES])
 @pytest.mark.parametrize("fold", [False, True], ids=["plain", "prescaled"])
 def test_mxfp4_attention_matches_oracle_on_dequantised_operands(vfa, oracle, name, w, fold):
     import torch
