@@ -140,7 +140,9 @@ int vsa_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LS
  *   reorder    1 = sink blocks, local blocks, then the rest (the method); 0 = ascending block
  *              order, the sink / local blocks keeping the exact-max update where they come
  *   freeze     1 = exact-max update on sink / local blocks only (the method); 0 = on every
- *              block (then n_sink = n_local = 0 with use_minit = 0 is allowed)
+ *              block (then n_sink = n_local = 0 with use_minit = 0 is allowed).  With freeze = 1 the
+ *              max needs a value before the first frozen block: use_minit = 0 with reorder = 0 and
+ *              n_sink = 0 (the first block in ascending order is an ordinary one) is rejected
  *   skip_threshold_nats  0 = no block skipping (skip_mask ignored); > 0 = the Alg. 2 skip test.
  *   rowskip    1 = Blasst_Rowskip: in a tile that is kept, a row that fails the threshold test is
  *              suppressed (scores -inf, its state untouched); needs skipping and freeze = 0

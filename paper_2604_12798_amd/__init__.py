@@ -31,6 +31,10 @@ def lib() -> ctypes.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2604_12798_amd.build`")
+        # torch first: it brings its own copy of the HIP runtime, and this library must bind to that one.  Loaded the
+        # other way round, the process holds two runtimes, the tensors live in one, this library's kernels are
+        # registered with the other, and every launch from here fails
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, i, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
         L.vfa_workspace_bytes.restype = sz

@@ -147,6 +147,9 @@ int vfa_vsa_common(int mode, const void* Q, const void* K, const void* V, void* 
     if (rc != VFA_OK) return rc;
     if (n_sink < 0 || n_local < 0) return VFA_ERR_INVALID_ARG;
     if (!use_minit && n_sink + n_local == 0 && freeze) return VFA_ERR_INVALID_ARG;
+    // ascending order, no seed, no sink block: a query block whose first key block is not one of its local ones would
+    // meet a frozen tile with the max still at -inf
+    if (!use_minit && !reorder && n_sink == 0 && freeze) return VFA_ERR_INVALID_ARG;
     if (repr_mode < 0 || repr_mode > 3) return VFA_ERR_INVALID_ARG;
     if (q_repr_mode < 0 || q_repr_mode > 3 || (q_repr_mode && use_minit != 1)) return VFA_ERR_INVALID_ARG;
     if (!(lazy_tau < 0.f) && !isfinite(lazy_tau)) return VFA_ERR_INVALID_ARG;   // negative = off; NaN / inf rejected

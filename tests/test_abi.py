@@ -83,6 +83,7 @@ def test_bad_arguments_are_rejected_before_launch(pkg):
     assert va(*base, 1, 1, 2, 0, 1, 1, 1, 0, -1.0, 0.0, 0.0, none, p, 1 << 20, none) == -1      # q_repr with caller's summaries
     assert va(*base, 1, 1, 1, 0, 2, 1, 1, 0, -1.0, 0.0, 0.0, none, p, 2048, none) == -1         # room for k_repr only
     assert va(*base, 0, 0, 0, 0, 0, 1, 1, 0, -1.0, 0.0, 0.0, none, p, 1 << 20, none) == -1      # frozen max would stay -inf
+    assert va(*base, 0, 2, 0, 0, 0, 0, 1, 0, -1.0, 0.0, 0.0, none, p, 1 << 20, none) == -1      # ascending, no seed, no sink: first tile frozen at -inf
     assert va(*base, 1, 1, 1, 0, 0, 0, 0, 0, -1.0, 0.0, -1.0, none, p, 1 << 20, none) == -1     # negative threshold
     assert va(*base, 0, 0, 0, 0, 0, 0, 0, 1, -1.0, 0.0, 0.0, none, p, 1 << 20, none) == -1      # row skip without a threshold
     assert va(*base, 1, 1, 1, 0, 0, 1, 1, 1, -1.0, 0.0, 4.0, none, p, 1 << 20, none) == -1      # row skip needs freeze = 0
