@@ -184,8 +184,9 @@ size_t vfa_decode_workspace_bytes(int B, int Hq, int d, int n_splits);
  * blocks), m_init = max_j scale * q . Krepr_j (or -inf); the cache is cut into n_splits ranges of
  * whole blocks; each range accumulates sum exp(s - m) and sum exp(s - m) v; the ranges are added in
  * index order (bit-identical results from run to run), divided, and LSE = m + ln l.  The result is
- * exact attention over the n_keys rows.  n_splits >= 1 (ranges may be empty; two (KV head, range) pairs fit
- * a compute unit at a time, so B * Hkv * n_splits of about twice the number of compute units is fastest); Hq / Hkv <= 32;
+ * exact attention over the n_keys rows.  n_splits >= 1 (ranges may be empty; up to four (KV head, range) pairs
+ * share a compute unit, and B * Hkv * n_splits of 1.5 to 4 times the number of compute units runs within a few
+ * percent of the best); Hq / Hkv <= 32;
  * block_n = 64; d in {64, 128}.  workspace: vfa_decode_workspace_bytes(...) bytes, 16-byte aligned,
  * contents irrelevant on entry.  VFA_ERR_INVALID_ARG for n_keys < 1 or > n_cap, for
  * use_minit == 0 with n_sink + n_local == 0, and for the pointer / size errors listed above. */

@@ -14,8 +14,9 @@ namespace {
 //                        sum exp(s - m) and sum exp(s - m) v over the split's key range
 //   decode_merge_kernel  per query head: ADD the partial sums (no max in the merge, because no split
 //                        ever rescales), divide, write O and LSE
-// The work is HBM bound (K and V are read once), so single-wave workgroups with a small tile ring (64 KiB of LDS, two
-// per CU) and the same tile helpers as the prefill kernels are enough.
+// The work is HBM bound (K and V are read once), so single-wave workgroups with the score and P.V helpers of the prefill
+// kernels are enough; what matters is how the tiles are fetched: into registers, with non-temporal loads, one tile ahead,
+// and from there into the two LDS tiles a workgroup owns (see decode_split_kernel).
 struct DecodeParams {
     const uint16_t* Q;      // [B, Hq, d]
     const uint16_t* K;      // [B, Hkv, n_cap, d]
@@ -79,18 +80,68 @@ __global__ __launch_bounds__(64) void decode_max_kernel(const DecodeParams p) {
     if (ql < p.Hq / p.Hkv && hh == 0) p.pm[((size_t)b * p.Hq + h) * p.n_splits + split] = m2;
 }
 
+// One 64-row tile, global -> registers with the tile mover's lane mapping (every instruction covers whole rows, 1 KiB
+// contiguous; the swizzle is applied on the global side), and registers -> LDS at the positions the LDS-direct mover
+// writes.  The loads are non-temporal: the cache is streamed through once per step and is larger than L2 and the
+// memory-side cache, and plain loads, which allocate there, cost 12 % of the stream's rate (LDS-direct loads another 7 %).
+// A whole tile (FULL) is addressed as a wave-uniform tile base plus a per-lane 32-bit offset that repeats every 16 rows
+// (offs[u & 3]: four values for K at d = 128, one otherwise); a ragged last tile clamps its rows.
+template <int D>
+__device__ __forceinline__ void tile_lane_offsets(bool is_v, int lane, uint32_t* offs) {
+    using T = Tile<D>;
+    constexpr int RPI = 1024 / T::ROWB;
+    const int cp = lane % T::CH;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int rr = RPI * u + lane / T::CH;
+        const int ch = is_v ? (cp ^ ((rr & (T::CH / 4 - 1)) << 2)) : (cp ^ (rr & (T::CH - 1)));
+        offs[u] = (uint32_t)((lane / T::CH) * T::ROWB + ch * 16);
+    }
+}
+template <int D, bool FULL>
+__device__ __forceinline__ void tile_to_regs(const uint16_t* base, int first_row, int row_limit, bool is_v, int lane,
+                                             const uint32_t* offs, u32x4* r) {
+    using T = Tile<D>;
+    constexpr int RPI = 1024 / T::ROWB, NI = BN / RPI;
+    if (FULL) {
+        const uint8_t* tb = reinterpret_cast<const uint8_t*>(base) + (size_t)first_row * T::ROWB;
+#pragma unroll
+        for (int u = 0; u < NI; ++u) r[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tb + (u * 1024 + offs[u & 3])));
+    } else {
+        const int cp = lane % T::CH;
+#pragma unroll
+        for (int u = 0; u < NI; ++u) {
+            const int rr = RPI * u + lane / T::CH;
+            const int ch = is_v ? (cp ^ ((rr & (T::CH / 4 - 1)) << 2)) : (cp ^ (rr & (T::CH - 1)));
+            const int gr = min(first_row + rr, row_limit - 1);
+            r[u] = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x4*>(reinterpret_cast<const uint8_t*>(base) + (size_t)gr * T::ROWB + ch * 16));
+        }
+    }
+}
+template <int D>
+__device__ __forceinline__ void regs_to_tile(uint8_t* dst, int lane, const u32x4* r) {
+    using T = Tile<D>;
+    constexpr int NI = BN / (1024 / T::ROWB);
+#pragma unroll
+    for (int u = 0; u < NI; ++u) *reinterpret_cast<u32x4*>(dst + u * 1024 + lane * 16) = r[u];
+}
+
+// The tiles are staged through registers: while tile t is worked on, V(t + 1) and K(t + 1), then K(t + 2), are in flight
+// in registers (the accumulation registers: loads and LDS writes take them directly), each requested one tile ahead of
+// its use, and LDS holds only the two tiles being read (32 KiB at d = 128; one wave per SIMD, four workgroups per CU).  The LDS executes a wave's instructions in
+// order: a tile is written over its predecessor behind the last read of that one, without a wait.  The steady loop runs
+// over whole tiles and has no branch between a load and its use, so that the compiler's wait counts stay exact (a load
+// that sits behind a branch makes it wait for everything at the join); the last one to three tiles, among them a
+// ragged one, take the same body with the missing requests compiled out.
 template <int D>
 __global__ __launch_bounds__(64) void decode_split_kernel(const DecodeParams p) {
     using T = Tile<D>;
     constexpr int DB = D / 32;
-    // K ring of three tiles filled two tiles ahead, V single buffered: 4 tiles = 64 KiB at d = 128, two workgroups per
-    // CU; no wait in the loop drains the load queue: each waits only for the tile it is about to read
-    __shared__ __attribute__((aligned(16))) uint8_t smem[4 * T::BYTES];
+    constexpr int NI = BN / (1024 / T::ROWB);
+    __shared__ __attribute__((aligned(16))) uint8_t smem[2 * T::BYTES];
     uint8_t* const Ks = smem;
-    uint8_t* const Vs = smem + 3 * T::BYTES;
-    constexpr int NI = BN / (1024 / T::ROWB);  // load instructions per tile (one wave)
-    constexpr int WAIT_BUT_1 = 0x0F70 | (NI & 15) | ((NI >> 4) << 14);              // s_waitcnt vmcnt(NI)
-    constexpr int WAIT_BUT_2 = 0x0F70 | ((2 * NI) & 15) | (((2 * NI) >> 4) << 14);  // s_waitcnt vmcnt(2 NI)
+    uint8_t* const Vs = smem + T::BYTES;
     const int lane = threadIdx.x, ql = lane & 31, hh = lane >> 5;
     const int split = blockIdx.x, bh = blockIdx.y;
     int b, h;
@@ -104,39 +155,65 @@ __global__ __launch_bounds__(64) void decode_split_kernel(const DecodeParams p) 
     const int Tc = (n_keys + BN - 1) / BN;
     const int per = (Tc + p.n_splits - 1) / p.n_splits;
     const int t_lo = split * per, t_hi = min(Tc, t_lo + per);
+    const int t_whole = min(t_hi, n_keys / BN);  // tiles below this index are whole
     const uint16_t* Kg = p.K + (size_t)bh * p.n_cap * D;
     const uint16_t* Vg = p.V + (size_t)bh * p.n_cap * D;
+    uint32_t offk[4], offv[4];
+    tile_lane_offsets<D>(false, lane, offk);
+    tile_lane_offsets<D>(true, lane, offv);
     f32x16 ot[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db) ot[db] = f32x16{0};
     float lsum = 0.f;
-    // requests in flight, oldest first, at the top of iteration t: K(t) [first iteration only], K(t + 1)
-    if (t_lo < t_hi) load_tile<D, 1>(Kg, t_lo * BN, n_keys, Ks, false, 0, lane);
-    if (t_lo + 1 < t_hi) load_tile<D, 1>(Kg, (t_lo + 1) * BN, n_keys, Ks + T::BYTES, false, 0, lane);
-    int slot = 0;
-    for (int t = t_lo; t < t_hi; ++t) {
-        // the V buffer's last readers (the P.V MFMAs of the previous tile) have all issued
-        load_tile<D, 1>(Vg, t * BN, n_keys, Vs, true, 0, lane);
-        const int s2 = slot >= 1 ? slot - 1 : 2;  // slot of K(t + 2) = (slot + 2) % 3
-        const bool more2 = t + 2 < t_hi, more1 = t + 1 < t_hi;
-        if (more2) load_tile<D, 1>(Kg, (t + 2) * BN, n_keys, Ks + s2 * T::BYTES, false, 0, lane);
-        // K(t) has landed when at most [K(t + 1)], V(t), [K(t + 2)] are still out
-        const int later = (more1 ? 1 : 0) + 1 + (more2 ? 1 : 0);
-        if (later == 3) __builtin_amdgcn_s_waitcnt(0x0F70 | ((3 * NI) & 15) | (((3 * NI) >> 4) << 14));
-        else if (later == 2) __builtin_amdgcn_s_waitcnt(WAIT_BUT_2);
-        else __builtin_amdgcn_s_waitcnt(WAIT_BUT_1);
-        __syncthreads();
+    u32x4 rk[NI], rv[NI];
+    // tile t.  On entry K(t) is in LDS, rv holds V(t) and, requested after it, rk holds K(t + 1) (HASK1).
+    // HASV1 / HASK2: tiles t + 1 / t + 2 exist; FULL: the tiles requested here are whole
+    auto body = [&](int t, auto hasv1_c, auto hask1_c, auto hask2_c, auto full_c) __attribute__((always_inline)) {
+        constexpr bool HASV1 = decltype(hasv1_c)::value, HASK1 = decltype(hask1_c)::value, HASK2 = decltype(hask2_c)::value;
+        constexpr bool FULL = decltype(full_c)::value;
         f32x16 st[2];
         uint32_t pk[16];
-        qk_tile_pipe<D>(Ks + slot * T::BYTES, qf, st, ql, hh);
-        softmax_tile<false, true, DB>(st, pk, ot, m2, lsum, p.c, t * BN, n_keys - 1, hh);  // frozen max, ragged tail masked
-        // V(t) has landed when at most K(t + 2) is still out (K(t + 1) was requested before V(t))
-        if (more2) __builtin_amdgcn_s_waitcnt(WAIT_BUT_1);
-        else __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();
+        qk_tile_pipe<D>(Ks, qf, st, ql, hh);
+        softmax_tile<false, !FULL, DB>(st, pk, ot, m2, lsum, p.c, t * BN, n_keys - 1, hh);  // frozen max; a ragged tail is masked
+        __builtin_amdgcn_sched_barrier(0);  // (requests and LDS writes go out where they are written, not where the scheduler likes them)
+        regs_to_tile<D>(Vs, lane, rv);  // V(t) has landed when only K(t + 1) is still out
+        if (HASV1) tile_to_regs<D, FULL>(Vg, (t + 1) * BN, n_keys, true, lane, offv, rv);
+        __builtin_amdgcn_sched_barrier(0);
         pv_tile_pipe<D>(Vs, pk, ot, lane, hh);
-        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this tile's LDS reads are done before its buffers are refilled
-        slot = slot == 2 ? 0 : slot + 1;
+        __builtin_amdgcn_sched_barrier(0);
+        if (HASK1) regs_to_tile<D>(Ks, lane, rk);  // K(t + 1) has landed when only V(t + 1) is still out
+        if (HASK2) tile_to_regs<D, FULL>(Kg, (t + 2) * BN, n_keys, false, lane, offk, rk);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    using Y = std::true_type;
+    using N_ = std::false_type;
+    if (t_lo < t_hi) {
+        tile_to_regs<D, false>(Kg, t_lo * BN, n_keys, false, lane, offk, rk);
+        tile_to_regs<D, false>(Vg, t_lo * BN, n_keys, true, lane, offv, rv);
+        __builtin_amdgcn_sched_barrier(0);
+        regs_to_tile<D>(Ks, lane, rk);
+        __builtin_amdgcn_sched_barrier(0);
+        int t = t_lo;
+        if (t + 2 < t_whole) {  // (the request for K(t + 1) is not behind a branch of its own: see above)
+            tile_to_regs<D, true>(Kg, (t + 1) * BN, n_keys, false, lane, offk, rk);
+            do {  // tiles t + 1 and t + 2 are whole and inside the range
+                body(t, Y{}, Y{}, Y{}, Y{});
+                ++t;
+            } while (t + 2 < t_whole);
+        } else if (t + 1 < t_hi) {
+            tile_to_regs<D, false>(Kg, (t + 1) * BN, n_keys, false, lane, offk, rk);
+        }
+        const int left = t_hi - t;  // 1 .. 3 (t_hi <= t_whole + 1)
+        if (left == 3) {
+            body(t, Y{}, Y{}, Y{}, N_{});
+            body(t + 1, Y{}, Y{}, N_{}, N_{});
+            body(t + 2, N_{}, N_{}, N_{}, N_{});
+        } else if (left == 2) {
+            body(t, Y{}, Y{}, N_{}, N_{});
+            body(t + 1, N_{}, N_{}, N_{}, N_{});
+        } else {
+            body(t, N_{}, N_{}, N_{}, N_{});
+        }
     }
     const float l = xhalf_sum(lsum);
     if (ql < p.Hq / p.Hkv) {
