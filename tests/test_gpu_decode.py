@@ -163,22 +163,41 @@ def test_decode_full_size_in_bench_configuration(vfa, oracle):
     assert err.max() <= O_MAX_ABS and err.mean() <= O_MEAN_ABS and lerr <= LSE_ABS
 
 
-def test_decode_with_per_sequence_lengths(vfa, oracle):
-    """A batch of four sequences of different lengths: summaries appended per sequence, one decode call;
+def _random_varlen_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    out = [("hand_picked", dict(B=4, Hq=8, Hkv=2, n_cap=1024, d=128), [1, 777, 1024, 130], 5)]
+    for i in range(n):
+        d = int(rng.choice([64, 128], p=[0.3, 0.7]))
+        g, Hkv, B = int(rng.choice([1, 2, 4, 8])), int(rng.choice([1, 2])), int(rng.integers(2, 6))
+        n_cap = int(rng.choice([256, 1024, 1984]))
+        lens = [int(x) for x in rng.integers(1, n_cap + 1, size=B)]
+        shape = dict(B=B, Hq=g * Hkv, Hkv=Hkv, n_cap=n_cap, d=d)
+        if d == 64:
+            shape["F"] = 4
+        out.append(("r%d_d%d_g%d_cap%d_%s" % (i, d, g, n_cap, "_".join(map(str, lens))), shape, lens, int(rng.integers(1, 20))))
+    return out
+
+
+VARLEN_CASES = _random_varlen_cases(6, 20260412)
+
+
+@pytest.mark.parametrize("name,shape,lens,n_splits", VARLEN_CASES, ids=[c[0] for c in VARLEN_CASES])
+def test_decode_with_per_sequence_lengths(vfa, oracle, name, shape, lens, n_splits):
+    """A batch of sequences of different lengths: summaries appended per sequence, one decode call;
     every sequence must equal the single-sequence oracle at its own length."""
     import torch
-    B, Hq, Hkv, n_cap, d = 4, 8, 2, 1024, 128
-    t = _cache(B=B, Hq=Hq, Hkv=Hkv, n_cap=n_cap, d=d)
+    B, Hq, Hkv, n_cap, d = shape["B"], shape["Hq"], shape["Hkv"], shape["n_cap"], shape["d"]
+    t = _cache(**shape)
     K, V = to_gpu(t["K"]), to_gpu(t["V"])
     Kh, Vh = wl.bf16_bits_to_f32(t["K"]), wl.bf16_bits_to_f32(t["V"])
-    lens = np.array([1, 777, 1024, 130], np.int32)
+    lens = np.array(lens, np.int32)
     R = torch.full((B, Hkv, n_cap // 64, d), 3.0, dtype=torch.bfloat16, device="cuda")
     half = torch.from_numpy(lens // 2).cuda()
     full = torch.from_numpy(lens).cuda()
     vfa.kblock_summary_append_varlen(K, R, torch.zeros(B, dtype=torch.int32, device="cuda"), half)
     vfa.kblock_summary_append_varlen(K, R, half, full)                  # grow each sequence to its length
     Qb = np.stack([t["Q"][b, :, lens[b] - 1] for b in range(B)])         # [B, Hq, d]: each sequence's newest token
-    O, L = vfa.decode_varlen_fwd(to_gpu(np.ascontiguousarray(Qb)), K, V, full, krepr=R, n_splits=5)
+    O, L = vfa.decode_varlen_fwd(to_gpu(np.ascontiguousarray(Qb)), K, V, full, krepr=R, n_splits=n_splits)
     torch.cuda.synchronize()
     got_R = R.float().cpu().numpy().astype(np.float64)
     for b in range(B):
